@@ -1,0 +1,186 @@
+/*
+ * startrail.h -- C ABI of the one-GPU ring-attention share (StarTrail hot path) for gfx950.
+ *
+ * The library computes what ONE GPU of a (concentric) ring computes for one
+ * attention layer in training: blockwise attention of a resident query shard
+ * against the KV chunks the ring delivers step by step, folded into a running
+ * (O, lse) state, and the matching backward accumulation of dQ, dK, dV.
+ * The ring itself is simulated by visiting chunks that are already resident
+ * in device memory; nothing here communicates.
+ *
+ * General rules for every entry point
+ *   - All tensor pointers are DEVICE pointers unless a parameter says "host".
+ *     Descriptor structs and the small integer tables are HOST memory and are
+ *     read before the call returns.
+ *   - The library allocates nothing and owns nothing: every buffer, including
+ *     workspaces, is the caller's.  Calls enqueue work on the given HIP stream
+ *     (a hipStream_t passed as void*, NULL = the default stream) and return
+ *     without synchronising.
+ *   - Errors are returned as st_status; nothing aborts or throws.  Arguments
+ *     are validated on the host before any launch; on error nothing is enqueued.
+ *     st_last_error() gives a text for the calling thread's last failure.
+ *   - Tensors Q, K, V, dO are 4-D [B, S, heads, D] views described by element
+ *     strides with the D dimension contiguous (st_tensor).  Base pointers and
+ *     strides must keep every row 16-byte aligned (ST_ERR_ALIGNMENT otherwise).
+ *   - Partial / running outputs are dense fp32: O-like [B, Sq, Hq, D],
+ *     lse-like [B, Hq, Sq]; chunk gradients [B, Sk, Hkv, D].
+ *   - Query head h reads KV head h / (Hq / Hkv).  Causal masking is by GLOBAL
+ *     token position: key t of a chunk is visible to query i iff
+ *     k_offset + t <= q_offset + i.  lse is the natural-log log-sum-exp of
+ *     scale * <q, k> over visible keys; a row with no visible key has O = 0
+ *     and lse = -inf.
+ *   - Supported: ST_F32 with D <= 256 (plain kernels), ST_BF16 with D == 128
+ *     or D == 64 (MFMA kernels, fp32 accumulation).  Anything else returns
+ *     ST_ERR_UNSUPPORTED.
+ */
+#ifndef STARTRAIL_H
+#define STARTRAIL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ST_OK = 0,
+  ST_ERR_INVALID_ARG = 1,   /* null pointer, negative size, Hq % Hkv != 0, bad layout (P, C, rank) ... */
+  ST_ERR_UNSUPPORTED = 2,   /* dtype / head_dim / size combination that has no kernel */
+  ST_ERR_ALIGNMENT = 3,     /* pointer or stride breaks the 16-byte row alignment */
+  ST_ERR_HIP = 4,           /* a HIP call or launch failed; see st_last_error() */
+  ST_ERR_WORKSPACE = 5      /* workspace missing or smaller than st_ring_workspace_bytes() */
+} st_status;
+
+typedef enum { ST_F32 = 0, ST_BF16 = 1 } st_dtype;
+
+/* How the driver walks the visit order. */
+typedef enum {
+  ST_RING_STEPWISE = 0,     /* one st_attn_block_fwd/bwd + st_attn_merge per visited chunk */
+  ST_RING_FUSED = 1         /* one launch per pass; the running state stays in registers */
+} st_ring_mode;
+
+#define ST_MAX_CHUNKS 256   /* most chunks one st_ring_* call accepts */
+
+/* 4-D view [B, S, heads, D]; strides in ELEMENTS; D contiguous (stride 1). */
+typedef struct {
+  void*   ptr;              /* device */
+  int64_t stride_b, stride_s, stride_h;
+} st_tensor;
+
+/* One (Q shard, KV chunk) pair: the operands of one ring iteration
+ * (Algorithm 1, the forward_iteration step). */
+typedef struct {
+  int32_t dtype;            /* st_dtype of Q, K, V, dO */
+  int32_t B, Hq, Hkv, D;
+  int32_t Sq, Sk;           /* tokens in the Q shard / in this chunk; Sk may be 0 */
+  int64_t q_offset;         /* global position of Q row 0 */
+  int64_t k_offset;         /* global position of chunk row 0 */
+  int32_t causal;           /* 0: every key visible; 1: visible iff k_offset+t <= q_offset+i */
+  float   scale;            /* softmax scale, normally 1/sqrt(D) (Section 2.1 attention equation) */
+} st_block_desc;
+
+/* One GPU's whole share: the Q shard plus the table of chunks the ring delivers
+ * (Section 3.2: after the team all-gather each delivered buffer is a run of
+ * sequence shards; here every shard is one chunk with its own base pointer). */
+typedef struct {
+  int32_t dtype;
+  int32_t B, Hq, Hkv, D;
+  int32_t Sq, Sk;           /* every chunk has Sk tokens */
+  int64_t q_offset;
+  int32_t causal;
+  float   scale;
+  int32_t n_chunks;         /* 1 .. ST_MAX_CHUNKS */
+  const void* const* k_ptr; /* host array [n_chunks] of device base pointers, chunk j = [B,Sk,Hkv,D] */
+  const void* const* v_ptr; /* host array [n_chunks] */
+  int64_t k_stride_b, k_stride_s, k_stride_h;   /* shared by all K chunks */
+  int64_t v_stride_b, v_stride_s, v_stride_h;   /* shared by all V chunks */
+  const int64_t* k_offset;  /* host array [n_chunks]: global position of row 0 of chunk j */
+} st_ring_desc;
+
+/* ---- ring iteration, forward (Algorithm 1: forward_iteration before its fold) ----
+ * Attention of the Q shard against ONE chunk.
+ *   o_part   fp32 [B,Sq,Hq,D]  (overwritten)   partial output, already divided by its own row sum
+ *   lse_part fp32 [B,Hq,Sq]    (overwritten)
+ * A fully masked chunk (or Sk == 0) is legal and writes O = 0, lse = -inf. */
+st_status st_attn_block_fwd(const st_block_desc* desc, const st_tensor* q, const st_tensor* k,
+                            const st_tensor* v, float* o_part, float* lse_part, void* hip_stream);
+
+/* ---- online-softmax fold / the arithmetic of ReduceScatter_combine (Algorithm 1;
+ * Section 3.2 "Forward Propagation": lse and O are updated step by step) ----
+ * In place: (o_acc, lse_acc) <- merge((o_acc, lse_acc), (o_part, lse_part)) with
+ *   lse' = log(exp(lse_acc) + exp(lse_part)),
+ *   O'   = exp(lse_acc - lse') O_acc + exp(lse_part - lse') O_part.
+ * A state with lse = -inf is empty (the neutral element; start from O = 0, lse = -inf).
+ * o_out_lowp (nullable): also write O' rounded to out_dtype, dense [B,Sq,Hq,D].
+ * o_acc/o_part fp32 [B,Sq,Hq,D]; lse_acc/lse_part fp32 [B,Hq,Sq].  o_part may not alias o_acc. */
+st_status st_attn_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                        int32_t B, int32_t Sq, int32_t Hq, int32_t D, int32_t out_dtype,
+                        void* o_out_lowp, void* hip_stream);
+
+/* ---- backward preparation (Section 3.2 "Backward Propagation": each iteration mirrors the
+ * FlashAttention backward, which needs Delta_i = <dO_i, O_i> of the FINAL merged O) ----
+ *   d_o      [B,Sq,Hq,D] in desc->dtype;  o: the final O, in o_dtype (ST_F32 or desc->dtype)
+ *   delta    fp32 [B,Hq,Sq] (overwritten).   Only B, Sq, Hq, D, dtype of desc are used. */
+st_status st_attn_delta(const st_block_desc* desc, const st_tensor* d_o, const st_tensor* o,
+                        int32_t o_dtype, float* delta, void* hip_stream);
+
+/* ---- ring iteration, backward (Section 3.2 "Backward Propagation") ----
+ * The Q shard (with its FINAL lse and Delta) meets ONE chunk:
+ *   P = exp(scale q k^T - lse),  dV += P^T dO,  dS = P o (dO v^T - Delta),
+ *   dQ += scale dS k,  dK += scale dS^T q   (dK, dV summed over the query heads of a KV group).
+ *   dq_acc fp32 [B,Sq,Hq,D]   ACCUMULATED (+=): the circulating query gradient
+ *   dk_acc, dv_acc fp32 [B,Sk,Hkv,D] ACCUMULATED (+=): stay with the chunk
+ * The caller zeroes the accumulators once.  dq_acc is updated with floating-point atomics
+ * in the bf16 path, so its low-order bits may differ from run to run. */
+st_status st_attn_block_bwd(const st_block_desc* desc, const st_tensor* q, const st_tensor* k,
+                            const st_tensor* v, const st_tensor* d_o, const float* lse_final,
+                            const float* delta, float* dq_acc, float* dk_acc, float* dv_acc,
+                            void* hip_stream);
+
+/* ---- fp32 -> storage dtype (round to nearest even), n contiguous elements ---- */
+st_status st_cast_from_f32(const float* src, void* dst, int64_t n, int32_t dst_dtype, void* hip_stream);
+
+/* ---- chunk-visit order of the concentric layout (appendix algorithms get_init_send and
+ * get_P2P_config; Section 3.2: teams of C, team groups of P/C^2 teams, sub-rings) ----
+ * For the Q shard of global rank `rank` (team rank/C): one GPU plays the C members of the team
+ * in turn; member a' walks its P/C^2 sub-ring iterations, each delivering the gathered KV of one
+ * team = C consecutive sequence shards.
+ *   shard_idx host [P] (out): sequence-shard index met at each of the P visits
+ *   member_of host [P] (out): team member (0..C-1) whose running state the visit folds into
+ * Requires C >= 1, C*C | P, 0 <= rank < P (else ST_ERR_INVALID_ARG).  C = 1 is the plain ring. */
+st_status st_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* shard_idx, int32_t* member_of);
+
+/* ---- driver: the whole share (Algorithm 1 loop + combine; backward loops of Section 3.2) ----
+ * order host [n_visit]: chunk indices into the desc tables, in visit order (each at most once).
+ * member_of host [n_visit] (nullable = all 0): running state each visit folds into; the member
+ *   states are merged at the end (the combine step).  Chunks lying entirely in the causal future
+ *   of the shard are skipped.
+ * Forward outputs: o_acc fp32 [B,Sq,Hq,D], lse fp32 [B,Hq,Sq] (overwritten); o_lowp nullable,
+ *   [B,Sq,Hq,D] in desc->dtype.
+ * workspace: device, >= st_ring_workspace_bytes(desc, mode, backward) bytes, 256-byte aligned. */
+size_t st_ring_workspace_bytes(const st_ring_desc* desc, int32_t mode, int32_t backward);
+
+st_status st_ring_fwd(const st_ring_desc* desc, const st_tensor* q, const int32_t* order,
+                      const int32_t* member_of, int32_t n_visit, int32_t mode,
+                      float* o_acc, float* lse, void* o_lowp,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward outputs (all ACCUMULATED, caller zeroes once): dq_acc fp32 [B,Sq,Hq,D];
+ * dk_acc, dv_acc host arrays [n_chunks] of device fp32 [B,Sk,Hkv,D] buffers (entries of chunks
+ * that are not visited may be NULL).  o: final O in o_dtype; lse_final from st_ring_fwd. */
+st_status st_ring_bwd(const st_ring_desc* desc, const st_tensor* q, const st_tensor* d_o,
+                      const st_tensor* o, int32_t o_dtype, const float* lse_final,
+                      const int32_t* order, int32_t n_visit, int32_t mode,
+                      float* dq_acc, float* const* dk_acc, float* const* dv_acc,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- misc ---- */
+const char* st_status_str(st_status s);
+const char* st_last_error(void);      /* thread-local text of the last failure, "" if none */
+int32_t     st_version(void);         /* major*10000 + minor*100 + patch */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STARTRAIL_H */

@@ -1,0 +1,13 @@
+"""One GPU's share of StarTrail / ring attention for gfx950 (MI355X).
+
+The work is done by hand-written HIP kernels behind a C ABI (``include/startrail.h``,
+``libstartrail.so``); this package only marshals arguments.  PyTorch tensors are used as
+device-memory handles and for the current HIP stream.  There is no CPU fallback: importing
+the bindings without the built library raises.
+"""
+from .api import (  # noqa: F401
+    ST_BF16, ST_F32, ST_RING_FUSED, ST_RING_STEPWISE, StarTrailError,
+    st_attn_block_bwd, st_attn_block_fwd, st_attn_delta, st_attn_merge, st_cast_from_f32,
+    st_last_error, st_ring_bwd, st_ring_fwd, st_ring_workspace_bytes, st_status_str,
+    st_version, st_visit_order, library_path,
+)

@@ -1,0 +1,412 @@
+// C-ABI layer: argument validation, dtype dispatch, the visit-order generator and the
+// driver that walks a chunk-visit order.  No arithmetic of the method lives here; every
+// step of the path runs in the HIP kernels behind the launch_* functions.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "st_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+st_status fail(st_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+st_status hip_fail(hipError_t e, const char* what) {
+  return fail(ST_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline size_t elem_size(int dtype) { return dtype == ST_BF16 ? 2 : 4; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+st_status check_shape(int dtype, int B, int Hq, int Hkv, int D, int Sq, int Sk) {
+  if (dtype != ST_F32 && dtype != ST_BF16) return fail(ST_ERR_INVALID_ARG, "unknown dtype %d", dtype);
+  if (B < 0 || Sq < 0 || Sk < 0) return fail(ST_ERR_INVALID_ARG, "negative size");
+  if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return fail(ST_ERR_INVALID_ARG, "need Hq %% Hkv == 0 (Hq=%d Hkv=%d)", Hq, Hkv);
+  if (D <= 0) return fail(ST_ERR_INVALID_ARG, "D must be positive");
+  if (dtype == ST_F32 && (D > 256 || D % 8 != 0)) return fail(ST_ERR_UNSUPPORTED, "fp32 path needs D <= 256 and D %% 8 == 0 (D=%d)", D);
+  if (dtype == ST_BF16 && D != 128 && D != 64) return fail(ST_ERR_UNSUPPORTED, "bf16 path is built for D = 64 or 128 (D=%d)", D);
+  if (B > 65535 || Hq > 65535) return fail(ST_ERR_UNSUPPORTED, "B and Hq must not exceed 65535");
+  return ST_OK;
+}
+
+// a [B,S,heads,D] view whose rows must be 16-byte aligned
+st_status check_view(const char* name, const void* ptr, int64_t sb, int64_t ss, int64_t sh, int dtype,
+                     int64_t n_elems) {
+  if (n_elems == 0) return ST_OK;
+  if (ptr == nullptr) return fail(ST_ERR_INVALID_ARG, "%s: null pointer", name);
+  const int64_t per16 = 16 / (int64_t)elem_size(dtype);
+  if (reinterpret_cast<uintptr_t>(ptr) % 16 != 0) return fail(ST_ERR_ALIGNMENT, "%s: base pointer is not 16-byte aligned", name);
+  if (sb % per16 || ss % per16 || sh % per16) return fail(ST_ERR_ALIGNMENT, "%s: strides must be multiples of %lld elements", name, (long long)per16);
+  if (sb < 0 || ss < 0 || sh < 0) return fail(ST_ERR_INVALID_ARG, "%s: negative stride", name);
+  return ST_OK;
+}
+
+st_status check_tensor(const char* name, const st_tensor* t, int dtype, int64_t n_elems) {
+  if (t == nullptr) return fail(ST_ERR_INVALID_ARG, "%s: null st_tensor", name);
+  return check_view(name, t->ptr, t->stride_b, t->stride_s, t->stride_h, dtype, n_elems);
+}
+
+st_status check_f32(const char* name, const void* p, int64_t n_elems) {
+  if (n_elems == 0) return ST_OK;
+  if (p == nullptr) return fail(ST_ERR_INVALID_ARG, "%s: null pointer", name);
+  if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return fail(ST_ERR_ALIGNMENT, "%s: not 16-byte aligned", name);
+  return ST_OK;
+}
+
+st::View view_of(const st_tensor* t) { return st::View{t->ptr, t->stride_b, t->stride_s, t->stride_h}; }
+
+st::Shape shape_of(const st_block_desc* d) {
+  return st::Shape{d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk, d->q_offset, d->causal ? 1 : 0, d->scale};
+}
+st::Shape shape_of(const st_ring_desc* d) {
+  return st::Shape{d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk, d->q_offset, d->causal ? 1 : 0, d->scale};
+}
+
+#define ST_TRY(expr)                  \
+  do {                                \
+    st_status _s = (expr);            \
+    if (_s != ST_OK) return _s;       \
+  } while (0)
+#define ST_HIP(expr, what)                        \
+  do {                                            \
+    hipError_t _e = (expr);                       \
+    if (_e != hipSuccess) return hip_fail(_e, what); \
+  } while (0)
+
+hipError_t launch_fwd(int dtype, const st::FwdArgs& a, hipStream_t s) {
+  return dtype == ST_BF16 ? st::launch_fwd_bf16(a, s) : st::launch_fwd_f32(a, s);
+}
+hipError_t launch_bwd(int dtype, const st::BwdArgs& a, hipStream_t s) {
+  return dtype == ST_BF16 ? st::launch_bwd_bf16(a, s) : st::launch_bwd_f32(a, s);
+}
+
+// chunk lies entirely in the causal future of the shard: nothing to compute
+inline bool chunk_invisible(const st_ring_desc* d, int j) {
+  return d->Sk == 0 || (d->causal && d->k_offset[j] > d->q_offset + d->Sq - 1);
+}
+
+st_status check_ring(const st_ring_desc* d, const st_tensor* q, const int32_t* order, int32_t n_visit) {
+  if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
+  ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  if (d->n_chunks < 1 || d->n_chunks > ST_MAX_CHUNKS) return fail(ST_ERR_INVALID_ARG, "n_chunks must be in 1..%d", ST_MAX_CHUNKS);
+  if (!d->k_ptr || !d->v_ptr || !d->k_offset) return fail(ST_ERR_INVALID_ARG, "null chunk table");
+  if (n_visit < 0 || n_visit > d->n_chunks) return fail(ST_ERR_INVALID_ARG, "n_visit out of range");
+  if (n_visit > 0 && order == nullptr) return fail(ST_ERR_INVALID_ARG, "null visit order");
+  const int64_t n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
+  bool seen[ST_MAX_CHUNKS] = {false};
+  for (int x = 0; x < n_visit; ++x) {
+    const int j = order[x];
+    if (j < 0 || j >= d->n_chunks) return fail(ST_ERR_INVALID_ARG, "order[%d] = %d is not a chunk index", x, j);
+    if (seen[j]) return fail(ST_ERR_INVALID_ARG, "chunk %d is visited twice", j);
+    seen[j] = true;
+    ST_TRY(check_view("k chunk", d->k_ptr[j], d->k_stride_b, d->k_stride_s, d->k_stride_h, d->dtype, n_kv));
+    ST_TRY(check_view("v chunk", d->v_ptr[j], d->v_stride_b, d->v_stride_s, d->v_stride_h, d->dtype, n_kv));
+  }
+  return check_tensor("q", q, d->dtype, (int64_t)d->B * d->Sq * d->Hq * d->D);
+}
+
+void set_table_strides(st::ChunkTable& t, const st_ring_desc* d) {
+  t.ksb = d->k_stride_b; t.kss = d->k_stride_s; t.ksh = d->k_stride_h;
+  t.vsb = d->v_stride_b; t.vss = d->v_stride_s; t.vsh = d->v_stride_h;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* st_status_str(st_status s) {
+  switch (s) {
+    case ST_OK: return "ok";
+    case ST_ERR_INVALID_ARG: return "invalid argument";
+    case ST_ERR_UNSUPPORTED: return "unsupported dtype / head_dim / size";
+    case ST_ERR_ALIGNMENT: return "misaligned pointer or stride";
+    case ST_ERR_HIP: return "HIP error";
+    case ST_ERR_WORKSPACE: return "workspace missing or too small";
+  }
+  return "unknown status";
+}
+
+const char* st_last_error(void) { return g_err; }
+int32_t st_version(void) { return 100; }
+
+st_status st_attn_block_fwd(const st_block_desc* d, const st_tensor* q, const st_tensor* k, const st_tensor* v,
+                            float* o_part, float* lse_part, void* hip_stream) {
+  if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
+  ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  const int64_t n_q = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
+  ST_TRY(check_tensor("q", q, d->dtype, n_q));
+  ST_TRY(check_tensor("k", k, d->dtype, n_kv));
+  ST_TRY(check_tensor("v", v, d->dtype, n_kv));
+  ST_TRY(check_f32("o_part", o_part, n_q));
+  ST_TRY(check_f32("lse_part", lse_part, n_q));
+  if (n_q == 0) return ST_OK;
+  st::FwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.s = shape_of(d);
+  a.q = view_of(q);
+  a.t.n = n_kv > 0 ? 1 : 0;
+  a.t.k[0] = k->ptr; a.t.v[0] = v->ptr; a.t.k_offset[0] = d->k_offset;
+  a.t.ksb = k->stride_b; a.t.kss = k->stride_s; a.t.ksh = k->stride_h;
+  a.t.vsb = v->stride_b; a.t.vss = v->stride_s; a.t.vsh = v->stride_h;
+  a.o = o_part; a.lse = lse_part; a.o_lowp = nullptr;
+  ST_HIP(launch_fwd(d->dtype, a, (hipStream_t)hip_stream), "st_attn_block_fwd launch");
+  return ST_OK;
+}
+
+st_status st_attn_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part, int32_t B,
+                        int32_t Sq, int32_t Hq, int32_t D, int32_t out_dtype, void* o_out_lowp, void* hip_stream) {
+  if (B < 0 || Sq < 0 || Hq <= 0 || D <= 0) return fail(ST_ERR_INVALID_ARG, "bad sizes");
+  if (D > 256 || D % 8 != 0) return fail(ST_ERR_UNSUPPORTED, "merge needs D <= 256 and D %% 8 == 0");
+  if (out_dtype != ST_F32 && out_dtype != ST_BF16) return fail(ST_ERR_INVALID_ARG, "unknown out_dtype");
+  const int64_t n = (int64_t)B * Sq * Hq * D;
+  ST_TRY(check_f32("o_acc", o_acc, n));
+  ST_TRY(check_f32("lse_acc", lse_acc, n));
+  ST_TRY(check_f32("o_part", o_part, n));
+  ST_TRY(check_f32("lse_part", lse_part, n));
+  if (o_out_lowp && reinterpret_cast<uintptr_t>(o_out_lowp) % 16) return fail(ST_ERR_ALIGNMENT, "o_out_lowp: not 16-byte aligned");
+  if (n > 0 && o_acc == o_part) return fail(ST_ERR_INVALID_ARG, "o_part aliases o_acc");
+  ST_HIP(st::launch_merge(o_acc, lse_acc, o_part, lse_part, B, Sq, Hq, D, o_out_lowp, out_dtype,
+                          (hipStream_t)hip_stream), "st_attn_merge launch");
+  return ST_OK;
+}
+
+st_status st_attn_delta(const st_block_desc* d, const st_tensor* d_o, const st_tensor* o, int32_t o_dtype,
+                        float* delta, void* hip_stream) {
+  if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
+  ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, 0));
+  if (o_dtype != ST_F32 && o_dtype != d->dtype) return fail(ST_ERR_INVALID_ARG, "o_dtype must be ST_F32 or the storage dtype");
+  const int64_t n = (int64_t)d->B * d->Sq * d->Hq * d->D;
+  ST_TRY(check_tensor("d_o", d_o, d->dtype, n));
+  ST_TRY(check_tensor("o", o, o_dtype, n));
+  ST_TRY(check_f32("delta", delta, n));
+  if (n == 0) return ST_OK;
+  ST_HIP(st::launch_delta(view_of(d_o), d->dtype, view_of(o), o_dtype, delta, d->B, d->Sq, d->Hq, d->D,
+                          (hipStream_t)hip_stream), "st_attn_delta launch");
+  return ST_OK;
+}
+
+st_status st_attn_block_bwd(const st_block_desc* d, const st_tensor* q, const st_tensor* k, const st_tensor* v,
+                            const st_tensor* d_o, const float* lse_final, const float* delta, float* dq_acc,
+                            float* dk_acc, float* dv_acc, void* hip_stream) {
+  if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
+  ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  const int64_t n_q = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
+  ST_TRY(check_tensor("q", q, d->dtype, n_q));
+  ST_TRY(check_tensor("d_o", d_o, d->dtype, n_q));
+  ST_TRY(check_tensor("k", k, d->dtype, n_kv));
+  ST_TRY(check_tensor("v", v, d->dtype, n_kv));
+  ST_TRY(check_f32("lse_final", lse_final, n_q));
+  ST_TRY(check_f32("delta", delta, n_q));
+  ST_TRY(check_f32("dq_acc", dq_acc, n_q));
+  ST_TRY(check_f32("dk_acc", dk_acc, n_kv));
+  ST_TRY(check_f32("dv_acc", dv_acc, n_kv));
+  if (n_q == 0 || n_kv == 0) return ST_OK;
+  if (d->causal && d->k_offset > d->q_offset + d->Sq - 1) return ST_OK;   // chunk entirely in the future
+  st::BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.s = shape_of(d);
+  a.q = view_of(q);
+  a.d_o = view_of(d_o);
+  a.t.n = 1;
+  a.t.k[0] = k->ptr; a.t.v[0] = v->ptr; a.t.k_offset[0] = d->k_offset;
+  a.t.ksb = k->stride_b; a.t.kss = k->stride_s; a.t.ksh = k->stride_h;
+  a.t.vsb = v->stride_b; a.t.vss = v->stride_s; a.t.vsh = v->stride_h;
+  a.lse = lse_final; a.delta = delta; a.dq = dq_acc; a.dk[0] = dk_acc; a.dv[0] = dv_acc;
+  ST_HIP(launch_bwd(d->dtype, a, (hipStream_t)hip_stream), "st_attn_block_bwd launch");
+  return ST_OK;
+}
+
+st_status st_cast_from_f32(const float* src, void* dst, int64_t n, int32_t dst_dtype, void* hip_stream) {
+  if (n < 0) return fail(ST_ERR_INVALID_ARG, "negative n");
+  if (dst_dtype != ST_F32 && dst_dtype != ST_BF16) return fail(ST_ERR_INVALID_ARG, "unknown dst_dtype");
+  ST_TRY(check_f32("src", src, n));
+  if (n > 0 && (dst == nullptr || reinterpret_cast<uintptr_t>(dst) % 16)) return fail(dst ? ST_ERR_ALIGNMENT : ST_ERR_INVALID_ARG, "dst: null or misaligned");
+  ST_HIP(st::launch_cast(src, dst, n, dst_dtype, (hipStream_t)hip_stream), "st_cast_from_f32 launch");
+  return ST_OK;
+}
+
+// Closed form of the schedule.  With S = P / C^2 teams per team group, the initial dispatch
+// leaves GPU (team t, member a) holding the gathered KV of team (t mod S) * C + a, and every
+// sub-ring step hands a buffer to the next team of the group, so at iteration i the GPU works on
+// team buffer ((t - i) mod S) * C + a, i.e. sequence shards [buffer * C, buffer * C + C).
+st_status st_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* shard_idx, int32_t* member_of) {
+  if (P < 1 || C < 1 || P % C != 0 || (P / C) % C != 0) return fail(ST_ERR_INVALID_ARG, "layout needs C >= 1 and C*C | P (P=%d C=%d)", P, C);
+  if (rank < 0 || rank >= P) return fail(ST_ERR_INVALID_ARG, "rank %d outside 0..%d", rank, P - 1);
+  if (!shard_idx || !member_of) return fail(ST_ERR_INVALID_ARG, "null output");
+  const int32_t S = P / (C * C);
+  const int32_t t = rank / C;
+  int32_t n = 0;
+  for (int32_t a = 0; a < C; ++a)
+    for (int32_t i = 0; i < S; ++i) {
+      const int32_t pos = ((t - i) % S + S) % S;
+      const int32_t buffer = pos * C + a;
+      for (int32_t c = 0; c < C; ++c, ++n) {
+        shard_idx[n] = buffer * C + c;
+        member_of[n] = a;
+      }
+    }
+  return ST_OK;
+}
+
+// Workspace layout (each block 256-byte aligned):
+//   forward, stepwise: partial O, partial lse, member O, member lse
+//   forward, fused:    (only when more than one launch is needed) partial O, partial lse
+//   backward:          Delta
+size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t backward) {
+  if (d == nullptr) return 0;
+  const size_t n_o = align_up((size_t)d->B * d->Sq * d->Hq * d->D * sizeof(float), 256);
+  const size_t n_l = align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256);
+  if (backward) return n_l;
+  if (mode == ST_RING_STEPWISE) return 2 * (n_o + n_l);
+  return n_o + n_l;
+}
+
+st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* order, const int32_t* member_of,
+                      int32_t n_visit, int32_t mode, float* o_acc, float* lse, void* o_lowp, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  ST_TRY(check_ring(d, q, order, n_visit));
+  if (mode != ST_RING_STEPWISE && mode != ST_RING_FUSED) return fail(ST_ERR_INVALID_ARG, "unknown mode %d", mode);
+  const int64_t n_o = (int64_t)d->B * d->Sq * d->Hq * d->D, n_l = (int64_t)d->B * d->Sq * d->Hq;
+  ST_TRY(check_f32("o_acc", o_acc, n_o));
+  ST_TRY(check_f32("lse", lse, n_o));
+  if (o_lowp && reinterpret_cast<uintptr_t>(o_lowp) % 16) return fail(ST_ERR_ALIGNMENT, "o_lowp: not 16-byte aligned");
+  if (n_o == 0) return ST_OK;
+  hipStream_t stream = (hipStream_t)hip_stream;
+
+  // visible chunks in visit order
+  int vis[ST_MAX_CHUNKS], mem[ST_MAX_CHUNKS], n = 0;
+  for (int x = 0; x < n_visit; ++x)
+    if (!chunk_invisible(d, order[x])) {
+      vis[n] = order[x];
+      mem[n] = member_of ? member_of[x] : 0;
+      ++n;
+    }
+
+  const size_t b_o = align_up((size_t)n_o * sizeof(float), 256), b_l = align_up((size_t)n_l * sizeof(float), 256);
+  const bool need_ws = mode == ST_RING_STEPWISE || n > st::kMaxTable;
+  if (need_ws) {
+    if (workspace == nullptr || workspace_bytes < st_ring_workspace_bytes(d, mode, 0)) return fail(ST_ERR_WORKSPACE, "forward workspace needs %zu bytes", st_ring_workspace_bytes(d, mode, 0));
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(ST_ERR_ALIGNMENT, "workspace: not 256-byte aligned");
+  }
+  char* ws = (char*)workspace;
+  float* part_o = (float*)ws;
+  float* part_l = (float*)(ws + b_o);
+
+  st::FwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.s = shape_of(d);
+  a.q = view_of(q);
+  set_table_strides(a.t, d);
+
+  if (mode == ST_RING_FUSED) {
+    // one launch per kMaxTable visible chunks; further launches go through a partial state + merge
+    if (n == 0) {
+      ST_HIP(st::launch_fill_state(o_acc, lse, n_o, n_l, stream), "state fill");
+      if (o_lowp) ST_HIP(st::launch_cast(o_acc, o_lowp, n_o, d->dtype, stream), "cast");
+      return ST_OK;
+    }
+    for (int x0 = 0; x0 < n; x0 += st::kMaxTable) {
+      const int cnt = n - x0 < st::kMaxTable ? n - x0 : st::kMaxTable;
+      a.t.n = cnt;
+      for (int x = 0; x < cnt; ++x) {
+        a.t.k[x] = d->k_ptr[vis[x0 + x]];
+        a.t.v[x] = d->v_ptr[vis[x0 + x]];
+        a.t.k_offset[x] = d->k_offset[vis[x0 + x]];
+      }
+      const bool single = n <= st::kMaxTable;
+      a.o = x0 == 0 ? o_acc : part_o;
+      a.lse = x0 == 0 ? lse : part_l;
+      a.o_lowp = single ? o_lowp : nullptr;
+      ST_HIP(launch_fwd(d->dtype, a, stream), "fused forward launch");
+      if (x0 > 0) {
+        const bool last = x0 + cnt >= n;
+        ST_HIP(st::launch_merge(o_acc, lse, part_o, part_l, d->B, d->Sq, d->Hq, d->D, last ? o_lowp : nullptr,
+                                d->dtype, stream), "merge launch");
+      }
+    }
+    return ST_OK;
+  }
+
+  // stepwise: per member a running state (Algorithm 1 loop), then the combine of the member states
+  float* mem_o = (float*)(ws + b_o + b_l);
+  float* mem_l = (float*)(ws + 2 * b_o + b_l);
+  ST_HIP(st::launch_fill_state(o_acc, lse, n_o, n_l, stream), "state fill");
+  a.t.n = 1;
+  a.o = part_o; a.lse = part_l; a.o_lowp = nullptr;
+  int x = 0;
+  while (x < n) {
+    const int member = mem[x];
+    ST_HIP(st::launch_fill_state(mem_o, mem_l, n_o, n_l, stream), "state fill");
+    for (; x < n && mem[x] == member; ++x) {
+      a.t.k[0] = d->k_ptr[vis[x]];
+      a.t.v[0] = d->v_ptr[vis[x]];
+      a.t.k_offset[0] = d->k_offset[vis[x]];
+      ST_HIP(launch_fwd(d->dtype, a, stream), "block forward launch");
+      ST_HIP(st::launch_merge(mem_o, mem_l, part_o, part_l, d->B, d->Sq, d->Hq, d->D, nullptr, d->dtype, stream), "merge launch");
+    }
+    ST_HIP(st::launch_merge(o_acc, lse, mem_o, mem_l, d->B, d->Sq, d->Hq, d->D, nullptr, d->dtype, stream), "combine launch");
+  }
+  if (o_lowp) ST_HIP(st::launch_cast(o_acc, o_lowp, n_o, d->dtype, stream), "cast");
+  return ST_OK;
+}
+
+st_status st_ring_bwd(const st_ring_desc* d, const st_tensor* q, const st_tensor* d_o, const st_tensor* o,
+                      int32_t o_dtype, const float* lse_final, const int32_t* order, int32_t n_visit, int32_t mode,
+                      float* dq_acc, float* const* dk_acc, float* const* dv_acc, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  ST_TRY(check_ring(d, q, order, n_visit));
+  if (mode != ST_RING_STEPWISE && mode != ST_RING_FUSED) return fail(ST_ERR_INVALID_ARG, "unknown mode %d", mode);
+  if (o_dtype != ST_F32 && o_dtype != d->dtype) return fail(ST_ERR_INVALID_ARG, "o_dtype must be ST_F32 or the storage dtype");
+  const int64_t n_o = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
+  ST_TRY(check_tensor("d_o", d_o, d->dtype, n_o));
+  ST_TRY(check_tensor("o", o, o_dtype, n_o));
+  ST_TRY(check_f32("lse_final", lse_final, n_o));
+  ST_TRY(check_f32("dq_acc", dq_acc, n_o));
+  if (n_visit > 0 && (!dk_acc || !dv_acc)) return fail(ST_ERR_INVALID_ARG, "null gradient tables");
+  if (n_o == 0) return ST_OK;
+  if (workspace == nullptr || workspace_bytes < st_ring_workspace_bytes(d, mode, 1)) return fail(ST_ERR_WORKSPACE, "backward workspace needs %zu bytes", st_ring_workspace_bytes(d, mode, 1));
+  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(ST_ERR_ALIGNMENT, "workspace: not 256-byte aligned");
+  hipStream_t stream = (hipStream_t)hip_stream;
+
+  int vis[ST_MAX_CHUNKS], n = 0;
+  for (int x = 0; x < n_visit; ++x)
+    if (!chunk_invisible(d, order[x])) {
+      const int j = order[x];
+      ST_TRY(check_f32("dk_acc[j]", dk_acc[j], n_kv));
+      ST_TRY(check_f32("dv_acc[j]", dv_acc[j], n_kv));
+      vis[n++] = j;
+    }
+
+  float* delta = (float*)workspace;
+  ST_HIP(st::launch_delta(view_of(d_o), d->dtype, view_of(o), o_dtype, delta, d->B, d->Sq, d->Hq, d->D, stream), "delta launch");
+
+  st::BwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.s = shape_of(d);
+  a.q = view_of(q);
+  a.d_o = view_of(d_o);
+  set_table_strides(a.t, d);
+  a.lse = lse_final; a.delta = delta; a.dq = dq_acc;
+  const int per_launch = mode == ST_RING_FUSED ? st::kMaxTable : 1;
+  for (int x0 = 0; x0 < n; x0 += per_launch) {
+    const int cnt = n - x0 < per_launch ? n - x0 : per_launch;
+    a.t.n = cnt;
+    for (int x = 0; x < cnt; ++x) {
+      const int j = vis[x0 + x];
+      a.t.k[x] = d->k_ptr[j]; a.t.v[x] = d->v_ptr[j]; a.t.k_offset[x] = d->k_offset[j];
+      a.dk[x] = dk_acc[j]; a.dv[x] = dv_acc[j];
+    }
+    ST_HIP(launch_bwd(d->dtype, a, stream), "backward launch");
+  }
+  return ST_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,196 @@
+// HBM-bound passes: log-sum-exp merge of two partial states, Delta = rowsum(dO * O),
+// fp32 -> storage-dtype casts and the (O = 0, lse = -inf) state fill.
+// One 16-byte vector per lane, rows never straddle a lane; grid sized to the data.
+#include "st_internal.h"
+
+namespace st {
+namespace {
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// ---- merge: thread = one float4 of one (b, i, h) row -----------------------------------------
+// A row occupies a power-of-two group of lanes (lanes beyond vec_per_row idle), so a row never
+// straddles a wavefront: every lane of the row has read lse_acc before lane 0 overwrites it.
+// Weights: w_acc = exp(lse_acc - lse'), w_part = exp(lse_part - lse'), lse' = max + log(sum).
+// A side with lse = -inf gets weight 0 without ever forming (-inf) - (-inf).
+template <bool kLowp>
+__global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, float* __restrict__ lse_acc,
+                                                    const float* __restrict__ o_part,
+                                                    const float* __restrict__ lse_part, int64_t n_rows,
+                                                    int32_t Sq, int32_t Hq, int32_t vec_per_row,
+                                                    int32_t lane_shift, uint2* __restrict__ o_lowp) {
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = tid >> lane_shift;             // (b * Sq + i) * Hq + h
+  const int32_t sub = (int32_t)(tid & ((1 << lane_shift) - 1));
+  if (row >= n_rows || sub >= vec_per_row) return;
+  const int64_t v = row * vec_per_row + sub;
+  const int32_t h = (int32_t)(row % Hq);
+  const int64_t bi = row / Hq;
+  const int32_t i = (int32_t)(bi % Sq);
+  const int64_t b = bi / Sq;
+  const int64_t sidx = (b * Hq + h) * Sq + i;
+  const float la = lse_acc[sidx], lp = lse_part[sidx];
+  const float m = fmaxf(la, lp);
+  float wa = 0.f, wp = 0.f, lnew = -INFINITY;
+  if (m != -INFINITY) {
+    const float ea = expf(la - m), ep = expf(lp - m);  // exp(-inf) = 0 for an empty side
+    const float sum = ea + ep;
+    lnew = m + logf(sum);
+    const float inv = 1.f / sum;
+    wa = ea * inv;
+    wp = ep * inv;
+  }
+  const float4 a = reinterpret_cast<const float4*>(o_acc)[v];
+  const float4 p = reinterpret_cast<const float4*>(o_part)[v];
+  float4 r;
+  r.x = wa * a.x + wp * p.x;
+  r.y = wa * a.y + wp * p.y;
+  r.z = wa * a.z + wp * p.z;
+  r.w = wa * a.w + wp * p.w;
+  reinterpret_cast<float4*>(o_acc)[v] = r;
+  if (kLowp) o_lowp[v] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
+  if (sub == 0) lse_acc[sidx] = lnew;
+}
+
+// fp32 "lowp" copy for the fp32 storage dtype
+__global__ __launch_bounds__(256) void copy_f32_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                       int64_t n_vec) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v < n_vec) dst[v] = src[v];
+}
+
+// ---- delta: 16 lanes per row, 16-byte loads, shuffle reduction inside the 16-lane group -------
+template <bool kDoBf16, bool kOBf16>
+__global__ __launch_bounds__(256) void delta_kernel(View d_o, View o, float* __restrict__ delta, int32_t B,
+                                                    int32_t Sq, int32_t Hq, int32_t D) {
+  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+  const int sub = threadIdx.x & 15;
+  const int64_t n_rows = (int64_t)B * Sq * Hq;
+  float acc = 0.f;
+  if (row < n_rows) {
+    const int32_t h = (int32_t)(row % Hq);
+    const int64_t bi = row / Hq;
+    const int32_t i = (int32_t)(bi % Sq);
+    const int64_t b = bi / Sq;
+    const int64_t off_d = b * d_o.sb + (int64_t)i * d_o.ss + (int64_t)h * d_o.sh;
+    const int64_t off_o = b * o.sb + (int64_t)i * o.ss + (int64_t)h * o.sh;
+    for (int d = sub * 8; d < D; d += 128) {           // 8 elements per lane per step
+      float x[8], y[8];
+      if (kDoBf16) {
+        const uint4 u = *reinterpret_cast<const uint4*>((const uint16_t*)d_o.ptr + off_d + d);
+        x[0] = bf16_lo(u.x); x[1] = bf16_hi(u.x); x[2] = bf16_lo(u.y); x[3] = bf16_hi(u.y);
+        x[4] = bf16_lo(u.z); x[5] = bf16_hi(u.z); x[6] = bf16_lo(u.w); x[7] = bf16_hi(u.w);
+      } else {
+        const float4 u0 = *reinterpret_cast<const float4*>((const float*)d_o.ptr + off_d + d);
+        const float4 u1 = *reinterpret_cast<const float4*>((const float*)d_o.ptr + off_d + d + 4);
+        x[0] = u0.x; x[1] = u0.y; x[2] = u0.z; x[3] = u0.w; x[4] = u1.x; x[5] = u1.y; x[6] = u1.z; x[7] = u1.w;
+      }
+      if (kOBf16) {
+        const uint4 u = *reinterpret_cast<const uint4*>((const uint16_t*)o.ptr + off_o + d);
+        y[0] = bf16_lo(u.x); y[1] = bf16_hi(u.x); y[2] = bf16_lo(u.y); y[3] = bf16_hi(u.y);
+        y[4] = bf16_lo(u.z); y[5] = bf16_hi(u.z); y[6] = bf16_lo(u.w); y[7] = bf16_hi(u.w);
+      } else {
+        const float4 u0 = *reinterpret_cast<const float4*>((const float*)o.ptr + off_o + d);
+        const float4 u1 = *reinterpret_cast<const float4*>((const float*)o.ptr + off_o + d + 4);
+        y[0] = u0.x; y[1] = u0.y; y[2] = u0.z; y[3] = u0.w; y[4] = u1.x; y[5] = u1.y; y[6] = u1.z; y[7] = u1.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc = fmaf(x[e], y[e], acc);
+    }
+  }
+#pragma unroll
+  for (int s = 8; s > 0; s >>= 1) acc += __shfl_xor(acc, s);
+  if (row < n_rows && sub == 0) {
+    const int32_t h = (int32_t)(row % Hq);
+    const int64_t bi = row / Hq;
+    delta[((bi / Sq) * Hq + h) * Sq + (bi % Sq)] = acc;
+  }
+}
+
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float4* __restrict__ src, uint2* __restrict__ dst,
+                                                        int64_t n_vec, const float* __restrict__ src_tail,
+                                                        uint16_t* __restrict__ dst_tail, int tail) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v < n_vec) {
+    const float4 x = src[v];
+    dst[v] = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+  } else if (v - n_vec < tail) {
+    dst_tail[v - n_vec] = (uint16_t)f32_to_bf16_rne(src_tail[v - n_vec]);
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_state_kernel(float* __restrict__ o, float* __restrict__ lse,
+                                                         int64_t n_o, int64_t n_lse) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (v < n_o) o[v] = 0.f;
+  if (v < n_lse) lse[v] = -INFINITY;
+}
+
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+}  // namespace
+
+hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part, int32_t B,
+                        int32_t Sq, int32_t Hq, int32_t D, void* o_lowp, int lowp_dtype, hipStream_t s) {
+  const int64_t n_rows = (int64_t)B * Sq * Hq;
+  const int64_t n_vec = n_rows * (D / 4);
+  if (n_vec == 0) return hipSuccess;
+  int lane_shift = 0;
+  while ((1 << lane_shift) < D / 4) ++lane_shift;      // D <= 256 -> at most 64 lanes per row
+  const unsigned blocks = blocks_for(n_rows << lane_shift);
+  if (o_lowp != nullptr && lowp_dtype == ST_BF16) {
+    hipLaunchKernelGGL(merge_kernel<true>, dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part,
+                       n_rows, Sq, Hq, D / 4, lane_shift, (uint2*)o_lowp);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(merge_kernel<false>, dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part,
+                     n_rows, Sq, Hq, D / 4, lane_shift, (uint2*)nullptr);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && o_lowp != nullptr) {
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n_vec)), dim3(256), 0, s, (const float4*)o_acc,
+                       (float4*)o_lowp, n_vec);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_delta(const View& d_o, int d_o_dtype, const View& o, int o_dtype, float* delta, int32_t B,
+                        int32_t Sq, int32_t Hq, int32_t D, hipStream_t s) {
+  const int64_t n_rows = (int64_t)B * Sq * Hq;
+  if (n_rows == 0) return hipSuccess;
+  const dim3 grid(blocks_for(n_rows * 16)), block(256);
+  const bool db = d_o_dtype == ST_BF16, ob = o_dtype == ST_BF16;
+  if (db && ob) hipLaunchKernelGGL((delta_kernel<true, true>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
+  else if (db) hipLaunchKernelGGL((delta_kernel<true, false>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
+  else if (ob) hipLaunchKernelGGL((delta_kernel<false, true>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
+  else hipLaunchKernelGGL((delta_kernel<false, false>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
+  return hipGetLastError();
+}
+
+hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  if (dst_dtype == ST_F32) return hipMemcpyAsync(dst, src, n * sizeof(float), hipMemcpyDeviceToDevice, s);
+  const int64_t n_vec = n / 4;
+  const int tail = (int)(n - n_vec * 4);
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n_vec + tail)), dim3(256), 0, s, (const float4*)src,
+                     (uint2*)dst, n_vec, src + n_vec * 4, (uint16_t*)dst + n_vec * 4, tail);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_state(float* o, float* lse, int64_t n_o, int64_t n_lse, hipStream_t s) {
+  const int64_t n = n_o > n_lse ? n_o : n_lse;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_state_kernel, dim3(blocks_for(n)), dim3(256), 0, s, o, lse, n_o, n_lse);
+  return hipGetLastError();
+}
+
+}  // namespace st

@@ -1,0 +1,69 @@
+// Internal launch interface between the C-ABI layer (st_api.cpp) and the HIP kernels.
+// Plain structs passed BY VALUE as kernel arguments: no device-side tables to allocate or copy.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/startrail.h"
+
+namespace st {
+
+constexpr int kMaxTable = 64;   // chunks one kernel launch can walk (fits the 4 KiB kernel-argument space)
+
+struct View {                   // [B, S, heads, D] view, element strides, D contiguous
+  const void* ptr;
+  int64_t sb, ss, sh;
+};
+
+struct Shape {
+  int32_t B, Hq, Hkv, D, Sq, Sk;
+  int64_t q_offset;
+  int32_t causal;
+  float scale;
+};
+
+// Chunks in visit order.  k/v are base pointers of [B,Sk,Hkv,D] views that share one stride set.
+struct ChunkTable {
+  int32_t n;
+  const void* k[kMaxTable];
+  const void* v[kMaxTable];
+  int64_t k_offset[kMaxTable];
+  int64_t ksb, kss, ksh, vsb, vss, vsh;
+};
+
+struct FwdArgs {
+  Shape s;
+  View q;
+  ChunkTable t;
+  float* o;        // fp32 [B,Sq,Hq,D]
+  float* lse;      // fp32 [B,Hq,Sq]
+  void* o_lowp;    // nullable, [B,Sq,Hq,D] in the storage dtype
+};
+
+struct BwdArgs {
+  Shape s;
+  View q, d_o;
+  ChunkTable t;
+  const float* lse;    // final
+  const float* delta;
+  float* dq;           // fp32 [B,Sq,Hq,D], +=
+  float* dk[kMaxTable];  // fp32 [B,Sk,Hkv,D] per table entry, +=
+  float* dv[kMaxTable];
+};
+
+// ---- launchers (each returns hipGetLastError() after the launch) ----
+hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
+hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
+hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
+
+hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                        int32_t B, int32_t Sq, int32_t Hq, int32_t D, void* o_lowp, int lowp_dtype,
+                        hipStream_t s);
+hipError_t launch_delta(const View& d_o, int d_o_dtype, const View& o, int o_dtype, float* delta,
+                        int32_t B, int32_t Sq, int32_t Hq, int32_t D, hipStream_t s);
+hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hipStream_t s);
+hipError_t launch_fill_state(float* o, float* lse, int64_t n_o, int64_t n_lse, hipStream_t s);
+
+}  // namespace st

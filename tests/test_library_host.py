@@ -1,0 +1,80 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its
+host logic (visit order, validation that fails before any launch) behaves."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2407_00611_amd as st
+from paper_2407_00611_amd import api
+from oracle import visit_order as ov
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "startrail.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(st_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(api.EXPORTS)
+    lib = C.CDLL(st.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strings():
+    assert st.st_version() >= 100
+    assert st.st_status_str(0) == "ok"
+    assert "alignment" in st.st_status_str(3) or "misaligned" in st.st_status_str(3)
+
+
+@pytest.mark.parametrize("P,C", [(1, 1), (4, 1), (4, 2), (8, 2), (16, 1), (16, 2), (16, 4), (32, 2), (32, 4),
+                                 (64, 1), (64, 2), (64, 4), (64, 8), (36, 3), (54, 3)])
+def test_visit_order_matches_cluster_simulation(P, C):
+    for rank in range(P):
+        assert st.st_visit_order(P, C, rank) == ov.visit_order(P, C, rank)
+
+
+def test_visit_order_rejects_bad_layouts():
+    for P, C, r in [(8, 3, 0), (8, 4, 0), (0, 1, 0), (8, 0, 0), (12, 4, 0), (8, 2, 8), (8, 2, -1)]:
+        with pytest.raises(st.StarTrailError) as e:
+            st.st_visit_order(P, C, r)
+        assert e.value.status == 1
+
+
+def _desc(**kw):
+    base = dict(dtype=0, B=1, Hq=2, Hkv=1, D=64, Sq=8, Sk=8, q_offset=0, k_offset=0, causal=1, scale=0.125)
+    base.update(kw)
+    return api.st_block_desc(*[base[k] for k, _ in api.st_block_desc._fields_])
+
+
+def _call_fwd(desc, q=0x1000, k=0x2000, v=0x3000, o=0x4000, lse=0x5000, strides=(1024, 128, 64)):
+    lib = api._lib
+    tq, tk, tv = (api.st_tensor(p, *strides) for p in (q, k, v))
+    return lib.st_attn_block_fwd(C.byref(desc), C.byref(tq), C.byref(tk), C.byref(tv), C.c_void_p(o),
+                                 C.c_void_p(lse), None)
+
+
+def test_validation_fails_before_any_launch():
+    """Fake device pointers: every call below must be rejected on the host."""
+    assert _call_fwd(_desc(Hq=3, Hkv=2)) == 1                 # Hq % Hkv
+    assert _call_fwd(_desc(dtype=7)) == 1
+    assert _call_fwd(_desc(Sq=-1)) == 1
+    assert _call_fwd(_desc(D=512)) == 2                        # no kernel
+    assert _call_fwd(_desc(dtype=1, D=96)) == 2
+    assert _call_fwd(_desc(), q=0x1004) == 3                   # misaligned base
+    assert _call_fwd(_desc(), strides=(1024, 130, 64)) == 3    # misaligned row stride
+    assert _call_fwd(_desc(), k=0) == 1                        # null
+    assert "null" in st.st_last_error()
+    assert api._lib.st_attn_block_fwd(None, None, None, None, None, None, None) == 1
+    assert api._lib.st_attn_merge(C.c_void_p(0x1000), C.c_void_p(0x2000), C.c_void_p(0x1000), C.c_void_p(0x3000),
+                                  1, 8, 2, 64, 0, None, None) == 1      # o_part aliases o_acc
+    assert api._lib.st_attn_merge(C.c_void_p(0x1000), C.c_void_p(0x2000), C.c_void_p(0x3000), C.c_void_p(0x4000),
+                                  1, 8, 2, 60, 0, None, None) == 2
+    assert api._lib.st_cast_from_f32(C.c_void_p(0x1000), C.c_void_p(0x2002), 16, 1, None) == 3
+
+
+def test_empty_problems_are_ok_without_a_gpu():
+    assert _call_fwd(_desc(Sq=0), q=0, o=0, lse=0) == 0
+    assert _call_fwd(_desc(B=0), q=0, k=0, v=0, o=0, lse=0) == 0

@@ -1,0 +1,70 @@
+"""Shared helpers for the GPU parity tests: device upload of the seeded inputs and the
+tolerance checks the benchmark contract states."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import synth_inputs as si
+
+
+def dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """Upload storage-exact fp32 values as a tensor of the storage dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype == "bf16":
+        return t.to(torch.bfloat16).cuda()        # exact: the values are already bf16-representable
+    return t.cuda()
+
+
+def bits_dev(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def upload(inp: si.Inputs):
+    w = inp.w
+    if w.dtype == "bf16":
+        q = bits_dev(inp.q_bits)
+        ks = [bits_dev(b) for b in inp.k_bits]
+        vs = [bits_dev(b) for b in inp.v_bits]
+        d_o = bits_dev(inp.d_o_bits) if inp.d_o_bits is not None else None
+    else:
+        q = dev(inp.q, "f32")
+        ks = [dev(x, "f32") for x in inp.k]
+        vs = [dev(x, "f32") for x in inp.v]
+        d_o = dev(inp.d_o, "f32") if inp.d_o is not None else None
+    return q, ks, vs, d_o
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def positions(w: si.Workload):
+    q_pos = np.arange(w.Sq, dtype=np.int64) + w.q_offset
+    k_pos = [np.arange(w.Sk, dtype=np.int64) + w.k_offset(j) for j in range(w.n_chunks)]
+    return q_pos, k_pos
+
+
+def assert_close(x, ref, dtype: str, what: str = "", lse: bool = False):
+    """fp32 path: ||x-ref||_F <= 1e-5 ||ref||_F and max|x-ref| <= 1e-5 max|ref|.
+    bf16 path: max|x-ref| <= 2e-2 and ||x-ref||_F <= 1e-2 ||ref||_F.
+    -inf entries (empty rows of an lse) must match exactly."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert x.shape == ref.shape, f"{what}: shape {x.shape} vs {ref.shape}"
+    inf_ref = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(x), inf_ref), f"{what}: -inf pattern differs"
+    assert not np.isnan(x).any(), f"{what}: NaN in result"
+    x = np.where(inf_ref, 0.0, x)
+    ref = np.where(inf_ref, 0.0, ref)
+    err = np.abs(x - ref)
+    fro_ref = np.linalg.norm(ref)
+    fro = np.linalg.norm(x - ref)
+    if dtype == "f32":
+        assert fro <= 1e-5 * fro_ref + 1e-30, f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-5"
+        assert err.max(initial=0.0) <= 1e-5 * np.abs(ref).max(initial=0.0) + 1e-30, \
+            f"{what}: max err {err.max():.3e} vs max|ref| {np.abs(ref).max():.3e}"
+    else:
+        assert err.max(initial=0.0) <= 2e-2, f"{what}: max abs err {err.max():.3e} > 2e-2"
+        if not lse:
+            assert fro <= 1e-2 * fro_ref + 1e-30, f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-2"
