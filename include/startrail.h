@@ -77,7 +77,7 @@ typedef struct {
   int64_t q_offset;         /* global position of Q row 0 */
   int64_t k_offset;         /* global position of chunk row 0 */
   int32_t causal;           /* 0: every key visible; 1: visible iff k_offset+t <= q_offset+i */
-  float   scale;            /* softmax scale, normally 1/sqrt(D) (Section 2.1 attention equation) */
+  float   scale;            /* softmax scale, finite and > 0, normally 1/sqrt(D) (Section 2.1 attention equation) */
 } st_block_desc;
 
 /* One GPU's whole share: the Q shard plus the table of chunks the ring delivers

@@ -26,6 +26,11 @@ st_status hip_fail(hipError_t e, const char* what) {
 inline size_t elem_size(int dtype) { return dtype == ST_BF16 ? 2 : 4; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+st_status check_scale(float scale) {
+  if (!(scale > 0.f) || scale > 3.0e38f) return fail(ST_ERR_INVALID_ARG, "scale must be finite and positive");
+  return ST_OK;
+}
+
 st_status check_shape(int dtype, int B, int Hq, int Hkv, int D, int Sq, int Sk) {
   if (dtype != ST_F32 && dtype != ST_BF16) return fail(ST_ERR_INVALID_ARG, "unknown dtype %d", dtype);
   if (B < 0 || Sq < 0 || Sk < 0) return fail(ST_ERR_INVALID_ARG, "negative size");
@@ -96,6 +101,7 @@ inline bool chunk_invisible(const st_ring_desc* d, int j) {
 st_status check_ring(const st_ring_desc* d, const st_tensor* q, const int32_t* order, int32_t n_visit) {
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  ST_TRY(check_scale(d->scale));
   if (d->n_chunks < 1 || d->n_chunks > ST_MAX_CHUNKS) return fail(ST_ERR_INVALID_ARG, "n_chunks must be in 1..%d", ST_MAX_CHUNKS);
   if (!d->k_ptr || !d->v_ptr || !d->k_offset) return fail(ST_ERR_INVALID_ARG, "null chunk table");
   if (n_visit < 0 || n_visit > d->n_chunks) return fail(ST_ERR_INVALID_ARG, "n_visit out of range");
@@ -141,6 +147,7 @@ st_status st_attn_block_fwd(const st_block_desc* d, const st_tensor* q, const st
                             float* o_part, float* lse_part, void* hip_stream) {
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  ST_TRY(check_scale(d->scale));
   const int64_t n_q = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
   ST_TRY(check_tensor("q", q, d->dtype, n_q));
   ST_TRY(check_tensor("k", k, d->dtype, n_kv));
@@ -198,6 +205,7 @@ st_status st_attn_block_bwd(const st_block_desc* d, const st_tensor* q, const st
                             float* dk_acc, float* dv_acc, void* hip_stream) {
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  ST_TRY(check_scale(d->scale));
   const int64_t n_q = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
   ST_TRY(check_tensor("q", q, d->dtype, n_q));
   ST_TRY(check_tensor("d_o", d_o, d->dtype, n_q));

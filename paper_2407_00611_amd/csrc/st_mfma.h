@@ -1,0 +1,91 @@
+// gfx950 building blocks shared by the bf16 forward and backward kernels:
+// MFMA wrappers and operand layouts, LDS transpose reads, bf16 packing, tile staging.
+//
+// v_mfma_f32_32x32x16_bf16 (one wavefront, lane l, half g = l / 32, r = l % 32):
+//   A (32 x 16): lane holds row r,    k = 8g .. 8g+7   (8 bf16)
+//   B (16 x 32): lane holds column r, k = 8g .. 8g+7   (8 bf16)
+//   C (32 x 32): lane holds column r, rows 8*(v/4) + 4g + v%4 for v = 0..15 (16 fp32)
+// The k order inside a contraction is free as long as A and B agree, which lets a C-layout
+// tile be fed back as a B operand without any cross-lane movement (see pack_c_as_b).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace st {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+#define ST_LDS __attribute__((address_space(3)))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// fp32 pair -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 f = {lo, hi};
+  bf16x2 h = __builtin_convertvector(f, bf16x2);
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+// Eight consecutive C-layout values (v = 8m .. 8m+7) as a B (or A) operand.
+// Slot e of the operand then stands for row 16m + 8*(e/4) + 4g + e%4 of the C tile.
+__device__ __forceinline__ bf16x8 pack_c_as_b(const f32x16& c, int m) {
+  u32x4 u;
+  u[0] = pack_bf16(c[8 * m + 0], c[8 * m + 1]);
+  u[1] = pack_bf16(c[8 * m + 2], c[8 * m + 3]);
+  u[2] = pack_bf16(c[8 * m + 4], c[8 * m + 5]);
+  u[3] = pack_bf16(c[8 * m + 6], c[8 * m + 7]);
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element (i % 4) of the four
+// 8-byte rows addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 of its group.
+__device__ __forceinline__ u32x2 lds_read_tr16(const ST_LDS char* p) {
+  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ST_LDS s16x4*)p);
+  return __builtin_bit_cast(u32x2, r);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const ST_LDS char* p) {
+  return *reinterpret_cast<const ST_LDS bf16x8*>(p);
+}
+
+// A-operand fragment of X^T for a row-major LDS tile X[row][col] (cols contiguous):
+// the lane gets column (col0 + l % 32) at the eight rows
+//   row0 + 4g + {0,1,2,3}  and  row0 + 8 + 4g + {0,1,2,3},
+// which is exactly the slot order pack_c_as_b produces for C rows 16m .. 16m+15 (row0 = 16m).
+// lane_off = byte offset of this lane's source row/col inside such a fragment (see tr_lane_offset).
+__device__ __forceinline__ bf16x8 lds_read_tr_frag(const ST_LDS char* tile, int row0, int col0, int stride,
+                                                   int lane_off) {
+  const ST_LDS char* p = tile + row0 * stride + col0 * 2 + lane_off;
+  u32x2 lo = lds_read_tr16(p);
+  u32x2 hi = lds_read_tr16(p + 8 * stride);
+  u32x4 u = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// source address of lane l inside a transposed fragment: row 4g + (l%16)/4, col 16*((l/16)%2) + 4*(l%4)
+__device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
+  const int g = lane >> 5, s = lane & 15, half = (lane >> 4) & 1;
+  return (4 * g + (s >> 2)) * stride + (16 * half + 4 * (s & 3)) * 2;
+}
+
+__device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
+__device__ __forceinline__ float xhalf_sum(float x) { return x + __shfl_xor(x, 32); }
+
+// XCD-aware block order: consecutive hardware block ids land on different XCDs (8 of them, each with
+// its own L2), so give every XCD a contiguous range of logical tiles.
+__device__ __forceinline__ int xcd_logical_block(int id, int total) {
+  return (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
+}
+
+}  // namespace st

@@ -1,0 +1,96 @@
+"""GPU parity, bf16 forward (MFMA path) against the fp64 oracle on the bf16-rounded inputs.
+Tolerance: max abs 2e-2 and relative Frobenius 1e-2 (lse: max abs 2e-2)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_00611_amd as st
+import synth_inputs as si
+from oracle import attention as oa
+from util import assert_close, host, positions, upload
+
+pytestmark = pytest.mark.gpu
+
+STEP_CASES = [
+    # name, B, Hq, Hkv, D, Sq, Sk, n, q_offset, causal
+    ("ragged_causal_gqa_d128", 2, 4, 2, 128, 300, 200, 3, 600 - 300, True),
+    ("noncausal_d128", 1, 2, 2, 128, 70, 130, 2, 0, False),
+    ("future_rows_d128", 1, 2, 1, 128, 100, 90, 2, -37, True),
+    ("ragged_causal_d64", 2, 3, 1, 64, 260, 150, 2, 40, True),
+    ("noncausal_d64", 1, 4, 4, 64, 515, 64, 3, 0, False),
+    ("one_row_one_key", 1, 1, 1, 128, 1, 1, 1, 0, True),
+]
+
+
+def _workload(c):
+    name, B, Hq, Hkv, D, Sq, Sk, n, q0, causal = c
+    return si.Workload(name, 80 + len(name), "bf16", B, Hq, Hkv, D, Sq, Sk, n, q0, causal, False)
+
+
+@pytest.mark.parametrize("case", STEP_CASES, ids=[c[0] for c in STEP_CASES])
+def test_block_fwd_then_merge(case):
+    w = _workload(case)
+    inp = si.make_inputs(w)
+    q, ks, vs, _ = upload(inp)
+    q_pos, k_pos = positions(w)
+    o_acc = torch.zeros((w.B, w.Sq, w.Hq, w.D), device="cuda")
+    lse_acc = torch.full((w.B, w.Hq, w.Sq), -float("inf"), device="cuda")
+    for j in range(w.n_chunks):
+        print(f"[{w.name}] block_fwd chunk {j}", flush=True)
+        o_p, l_p = st.st_attn_block_fwd(q, ks[j], vs[j], w.q_offset, w.k_offset(j), w.causal, w.scale)
+        o_pr, l_pr = oa.block_forward(inp.q, inp.k[j], inp.v[j], q_pos, k_pos[j], w.causal, w.scale)
+        assert_close(host(o_p), o_pr, "bf16", f"o_part[{j}]")
+        assert_close(host(l_p), l_pr, "bf16", f"lse_part[{j}]", lse=True)
+        st.st_attn_merge(o_acc, lse_acc, o_p, l_p)
+    o_mono, lse_mono = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    assert_close(host(o_acc), o_mono, "bf16", "o vs monolithic")
+    assert_close(host(lse_acc), lse_mono, "bf16", "lse vs monolithic", lse=True)
+
+
+@pytest.mark.parametrize("mode", [st.ST_RING_STEPWISE, st.ST_RING_FUSED], ids=["stepwise", "fused"])
+@pytest.mark.parametrize("D", [128, 64])
+def test_ring_forward_small(mode, D):
+    w = si.Workload("ring_bf16_small", 85, "bf16", 1, 4, 2, D, 200, 200, 8, 5 * 200, True, False)
+    inp = si.make_inputs(w)
+    q, ks, vs, _ = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    for C in (1, 2):
+        order, members = st.st_visit_order(8, C, 5)
+        print(f"[ring small D={D}] mode {mode} C={C} order {order}", flush=True)
+        o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, mode)
+        assert_close(host(o), o_ref, "bf16", "o")
+        assert_close(host(lse), lse_ref, "bf16", "lse", lse=True)
+        assert_close(host(o_low), o_ref, "bf16", "o bf16")
+        assert torch.equal(o_low, o.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("mode", [st.ST_RING_STEPWISE, st.ST_RING_FUSED], ids=["stepwise", "fused"])
+def test_config2_forward(mode):
+    w = si.paper_workloads()[1]
+    inp = si.make_inputs(w)
+    q, ks, vs, _ = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    order, members = st.st_visit_order(w.ring_P, w.ring_C, w.ring_rank)
+    print(f"[cfg2] mode {mode}", flush=True)
+    o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, mode)
+    torch.cuda.synchronize()
+    print("[cfg2] oracle", flush=True)
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    assert_close(host(o), o_ref, "bf16", "o")
+    assert_close(host(lse), lse_ref, "bf16", "lse", lse=True)
+    assert_close(host(o_low), o_ref, "bf16", "o bf16")
+
+
+def test_empty_and_future_chunks():
+    w = _workload(("edge", 1, 2, 1, 128, 70, 40, 1, 0, True))
+    inp = si.make_inputs(w)
+    q, ks, vs, _ = upload(inp)
+    o, l = st.st_attn_block_fwd(q, ks[0], vs[0], 0, 1000, True, w.scale)          # chunk in the future
+    assert not o.any() and torch.isneginf(l).all()
+    o, l = st.st_attn_block_fwd(q, ks[0][:, :0], vs[0][:, :0], 0, 0, False, w.scale)   # Sk = 0
+    assert not o.any() and torch.isneginf(l).all()
+    o, l, ol = st.st_ring_fwd(q, ks, vs, 0, [1000], True, w.scale, [0])            # whole share invisible
+    assert not o.any() and torch.isneginf(l).all() and not ol.any()
