@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark: one GPU's share of ring attention, forward + backward, on one MI355X.
+
+A step = one pass of the whole hot path over the workload, with all inputs resident in HBM:
+  visit order -> ring forward (all chunks, online-softmax state, O in fp32 and bf16, lse)
+  -> zero the gradient accumulators -> Delta -> ring backward (dK/dV and dQ kernels)
+  -> fp32 -> bf16 casts of dQ, dK, dV.
+The workload is benchmark configuration 4 (GQA 32/8 heads, D=128, Q shard 4096, 32 chunks of
+4096 keys, causal, last rank of a P=32 / C=4 concentric layout) with synthetic N(0,1) bf16 data.
+
+Prints ONE JSON line (see the keys below).  `value` is algorithmic attention TFLOP/s: 4*D per
+visible (query, key) pair forward and 10*D backward, masked pairs and recomputation earn nothing.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk/CU x 2.4 GHz
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4)")
+    ap.add_argument("--mode", choices=["fused", "stepwise"], default="fused")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures ONE GPU's share of the ring; runs with more than one GPU are not part of "
+              "this build (the ring is simulated over chunks resident in HBM). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2407_00611_amd as st
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback for the HIP path)", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    w = si.paper_workloads()[args.config - 1]
+    mode = st.ST_RING_FUSED if args.mode == "fused" else st.ST_RING_STEPWISE
+    bf16 = w.dtype == "bf16"
+    storage = st.ST_BF16 if bf16 else st.ST_F32
+
+    # ---- inputs: generated on the host from the seeded generator, uploaded once -------------------
+    t0 = time.time()
+    inp = si.make_inputs(w, threads=min(16, os.cpu_count() or 8), keep_f32=not bf16)
+
+    def up(bits, f32):
+        if bf16:
+            return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(f32).cuda()
+
+    q = up(inp.q_bits, inp.q)
+    ks = [up(inp.k_bits[j] if bf16 else None, inp.k[j]) for j in range(w.n_chunks)]
+    vs = [up(inp.v_bits[j] if bf16 else None, inp.v[j]) for j in range(w.n_chunks)]
+    d_o = up(inp.d_o_bits, inp.d_o) if w.backward else None
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    if w.ring_P:
+        order, members = st.st_visit_order(w.ring_P, w.ring_C, w.ring_rank)
+    else:
+        order, members = list(range(w.n_chunks)), None
+    gen_s = time.time() - t0
+
+    # ---- resident outputs and workspaces (allocated once, outside the timed region) -----------------
+    dev = q.device
+    o_acc = torch.empty((w.B, w.Sq, w.Hq, w.D), dtype=torch.float32, device=dev)
+    lse = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device=dev)
+    o_low = torch.empty((w.B, w.Sq, w.Hq, w.D), dtype=q.dtype, device=dev)
+    ws_f = torch.empty(st.st_ring_workspace_bytes(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, mode, False) + 256,
+                       dtype=torch.uint8, device=dev)
+    if w.backward:
+        ws_b = torch.empty(st.st_ring_workspace_bytes(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, mode, True) + 256,
+                           dtype=torch.uint8, device=dev)
+        dq = torch.empty_like(o_acc)
+        dkv = torch.empty((2, w.n_chunks) + tuple(ks[0].shape), dtype=torch.float32, device=dev)
+        dk = [dkv[0, j] for j in range(w.n_chunks)]
+        dv = [dkv[1, j] for j in range(w.n_chunks)]
+        dq_low = torch.empty_like(o_low)
+        dkv_low = torch.empty(dkv.shape, dtype=q.dtype, device=dev)
+
+    def step():
+        st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, mode,
+                       o_acc=o_acc, lse=lse, o_lowp=o_low, workspace=ws_f)
+        if w.backward:
+            dq.zero_()
+            dkv.zero_()
+            st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv,
+                           mode, workspace=ws_b)
+            st.st_cast_from_f32(dq, storage, dq_low)
+            st.st_cast_from_f32(dkv, storage, dkv_low)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per-kernel durations with HIP events on the launch stream (separate, untimed steps) ---------
+    prof_steps = max(1, min(args.steps, 5))
+    torch.cuda.synchronize()
+    st.st_profile_begin()
+    for _ in range(prof_steps):
+        step()
+    kernels = st.st_profile_end()
+
+    fwd_flop, bwd_flop = si.algorithmic_flop(w)
+    total_flop = fwd_flop + bwd_flop
+    value = total_flop / (ms_per_step * 1e-3) / 1e12
+    pairs = si.visible_pairs(w) * w.Hq * w.B
+    # algorithmic work of each MFMA kernel per launch: forward = QK^T and PV; the dK/dV kernel owns
+    # S, dP, dV, dK (four of the five backward contractions); the dQ kernel owns dQ (its recomputed
+    # S and dP earn nothing)
+    algo = {"fwd_bf16": 4 * w.D * pairs, "bwd_dkv_bf16": 8 * w.D * pairs, "bwd_dq_bf16": 2 * w.D * pairs,
+            "fwd_f32": 4 * w.D * pairs, "bwd_dkv_f32": 8 * w.D * pairs, "bwd_dq_f32": 2 * w.D * pairs}
+    per_kernel = {}
+    for name, (launches, total_ms) in kernels.items():
+        avg = total_ms / max(launches, 1)
+        per_kernel[name] = {"launches_per_step": launches / prof_steps, "avg_ms": round(avg, 4)}
+        if name in algo and mode == st.ST_RING_FUSED:
+            per_kernel[name]["algorithmic_tflops"] = round(algo[name] / (avg * 1e-3) / 1e12, 1)
+    dom = max((n for n in kernels if n in algo), key=lambda n: kernels[n][1], default=None)
+    roofline = None
+    if dom is not None:
+        launches, total_ms = kernels[dom]
+        step_ms = total_ms / prof_steps                        # all launches of that kernel in one step
+        achieved = algo[dom] / (step_ms * 1e-3) / 1e12
+        peak = PEAK_BF16_TFLOPS if bf16 else 157.3
+        roofline = {"kernel": dom, "bound": "mfma" if bf16 else "alu", "achieved": round(achieved, 1), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                    "avg_launch_ms": round(total_ms / max(launches, 1), 4)}
+
+    out = {
+        "metric": "fwd+bwd attention TFLOP/s on 1 MI355X + % of bf16 MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "Sq": w.Sq, "Sk": w.Sk,
+                   "n_chunks": w.n_chunks, "causal": w.causal, "q_offset": w.q_offset, "mode": args.mode,
+                   "visit_order": f"P={w.ring_P},C={w.ring_C},rank={w.ring_rank}" if w.ring_P else "natural",
+                   "passes": "fwd+bwd" if w.backward else "fwd"},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "algorithmic_tflop": {"fwd": round(fwd_flop / 1e12, 4), "bwd": round(bwd_flop / 1e12, 4)},
+        "roofline": roofline,
+        "kernels": per_kernel,
+        "input_generation_s": round(gen_s, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(w, inp) -> dict:
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of the same
+    workload: forward + backward of a few seeded query rows of the first KV group against all keys."""
+    import synth_inputs as si
+    from oracle import attention as oa
+
+    rows_per_head = 128 if w.Sq >= 128 else w.Sq
+    G = w.Hq // w.Hkv
+    heads = list(range(min(G, w.Hq)))                      # the query heads of KV head 0
+    k_pos = [np.arange(w.Sk, dtype=np.int64) + w.k_offset(j) for j in range(w.n_chunks)]
+
+    def kv_head0(bits_list, f32_list):
+        if w.dtype == "bf16":
+            return [si.bf16_bits_to_f32(b[:, :, 0:1, :]) for b in bits_list]
+        return [x[:, :, 0:1, :] for x in f32_list]
+
+    k0, v0 = kv_head0(inp.k_bits, inp.k), kv_head0(inp.v_bits, inp.v)
+    pairs = 0
+    t0 = time.perf_counter()
+    for h in heads:
+        rows = si.sampled_rows(w, h, rows_per_head)
+        q_pos = rows + w.q_offset
+        qh = inp.q[:, rows, h:h + 1, :]
+        oa.attention_forward(qh, k0, v0, q_pos, k_pos, w.causal, w.scale)
+        if w.backward:
+            oa.attention_backward(qh, k0, v0, inp.d_o[:, rows, h:h + 1, :], q_pos, k_pos, w.causal, w.scale)
+        pairs += int(np.clip(q_pos + 1, 0, w.N).sum()) if w.causal else len(rows) * w.N
+    secs = time.perf_counter() - t0
+    flop = (4 + (10 if w.backward else 0)) * w.D * pairs * w.B
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": round(flop / secs / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{rows_per_head} seeded query rows of each of {len(heads)} heads (KV head 0) against all "
+                      f"{w.N} keys, fwd{'+bwd' if w.backward else ''}, numpy fp64",
+            "seconds": round(secs, 2)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -175,6 +175,20 @@ st_status st_ring_bwd(const st_ring_desc* desc, const st_tensor* q, const st_ten
                       float* dq_acc, float* const* dk_acc, float* const* dv_acc,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- per-kernel timing for benchmarks (not part of the method) ----
+ * Between st_profile_begin() and st_profile_end() the library records a HIP event on the launch
+ * stream before and after every kernel it launches (this creates hipEvent_t objects; at most 4096
+ * launches are recorded, later ones run untimed).  st_profile_end() waits for the recorded events,
+ * sums the durations per kernel name into out[0 .. *n_entries) (host memory, at most max_entries
+ * entries) and stops recording.  Process-wide; not meant to be used from several threads at once. */
+typedef struct {
+  char    name[48];
+  int32_t launches;
+  float   total_ms;
+} st_profile_entry;
+st_status st_profile_begin(void);
+st_status st_profile_end(st_profile_entry* out, int32_t max_entries, int32_t* n_entries);
+
 /* ---- misc ---- */
 const char* st_status_str(st_status s);
 const char* st_last_error(void);      /* thread-local text of the last failure, "" if none */

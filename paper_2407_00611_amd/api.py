@@ -45,13 +45,17 @@ class st_ring_desc(C.Structure):
                 ("k_offset", C.POINTER(C.c_int64))]
 
 
+class st_profile_entry(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("total_ms", C.c_float)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
 
 def _load() -> C.CDLL:
     if not os.path.exists(_LIB_PATH):
-        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2407_00611_amd.build` "
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python paper_2407_00611_amd/build.py` "
                           "(there is no CPU fallback)")
     lib = C.CDLL(_LIB_PATH)
     T, D, R = C.POINTER(st_tensor), C.POINTER(st_block_desc), C.POINTER(st_ring_desc)
@@ -67,6 +71,8 @@ def _load() -> C.CDLL:
         "st_ring_fwd": (C.c_int, [R, T, i32p, i32p, C.c_int32, C.c_int32, f32p, f32p, vp, vp, C.c_size_t, vp]),
         "st_ring_bwd": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
+        "st_profile_begin": (C.c_int, []),
+        "st_profile_end": (C.c_int, [C.POINTER(st_profile_entry), C.c_int32, C.POINTER(C.c_int32)]),
         "st_status_str": (C.c_char_p, [C.c_int]),
         "st_last_error": (C.c_char_p, []),
         "st_version": (C.c_int32, []),
@@ -79,7 +85,8 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_delta", "st_attn_block_bwd", "st_cast_from_f32",
-           "st_visit_order", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_status_str",
+           "st_visit_order", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_profile_begin",
+           "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
 
@@ -140,6 +147,18 @@ def st_status_str(status: int) -> str:
 
 def st_last_error() -> str:
     return _lib.st_last_error().decode()
+
+
+def st_profile_begin() -> None:
+    _check(_lib.st_profile_begin(), "st_profile_begin")
+
+
+def st_profile_end() -> dict:
+    """{kernel name: (launches, total_ms)} of everything launched since st_profile_begin()."""
+    buf = (st_profile_entry * 32)()
+    n = C.c_int32(0)
+    _check(_lib.st_profile_end(buf, 32, C.byref(n)), "st_profile_end")
+    return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(n.value)}
 
 
 def st_attn_block_fwd(q, k, v, q_offset: int, k_offset: int, causal: bool, scale: float,

@@ -1,6 +1,6 @@
 """Builds libstartrail.so (gfx950) in-tree with hipcc.
 
-    python -m paper_2407_00611_amd.build
+    python paper_2407_00611_amd/build.py      (run as a script: importing the package needs the built library)
 
 Every source is compiled on every call; objects go to ``_build/`` (git-ignored).
 """

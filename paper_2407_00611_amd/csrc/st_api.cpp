@@ -5,9 +5,22 @@
 #include <cstdio>
 #include <cstring>
 
+#include <mutex>
+#include <vector>
+
 #include "st_internal.h"
 
 namespace {
+
+// ---- event profiler state ----
+struct ProfRec {
+  const char* name;
+  hipEvent_t start, stop;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+constexpr size_t kProfMax = 4096;
 
 thread_local char g_err[512] = "";
 
@@ -126,7 +139,71 @@ void set_table_strides(st::ChunkTable& t, const st_ring_desc* d) {
 
 }  // namespace
 
+namespace st {
+
+ProfScope::ProfScope(const char* name, hipStream_t s) : slot(-1), stream(s) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (!g_prof_on || g_prof.size() >= kProfMax) return;
+  ProfRec r{name, nullptr, nullptr};
+  if (hipEventCreate(&r.start) != hipSuccess) return;
+  if (hipEventCreate(&r.stop) != hipSuccess) {
+    (void)hipEventDestroy(r.start);
+    return;
+  }
+  (void)hipEventRecord(r.start, s);
+  g_prof.push_back(r);
+  slot = (int)g_prof.size() - 1;
+}
+
+ProfScope::~ProfScope() {
+  if (slot < 0) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (slot < (int)g_prof.size()) (void)hipEventRecord(g_prof[slot].stop, stream);
+}
+
+}  // namespace st
+
 extern "C" {
+
+st_status st_profile_begin(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (auto& r : g_prof) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.clear();
+  g_prof_on = true;
+  return ST_OK;
+}
+
+st_status st_profile_end(st_profile_entry* out, int32_t max_entries, int32_t* n_entries) {
+  if (!out || !n_entries || max_entries < 0) return fail(ST_ERR_INVALID_ARG, "null output");
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = false;
+  int32_t n = 0;
+  st_status status = ST_OK;
+  for (auto& r : g_prof) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+    if (e != hipSuccess) status = hip_fail(e, "st_profile_end");
+    int32_t k = 0;
+    while (k < n && strncmp(out[k].name, r.name, sizeof(out[k].name) - 1) != 0) ++k;
+    if (k == n) {
+      if (n >= max_entries) continue;
+      memset(&out[n], 0, sizeof(out[n]));
+      strncpy(out[n].name, r.name, sizeof(out[n].name) - 1);
+      ++n;
+    }
+    out[k].launches += 1;
+    out[k].total_ms += ms;
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.clear();
+  *n_entries = n;
+  return status;
+}
 
 const char* st_status_str(st_status s) {
   switch (s) {

@@ -147,6 +147,7 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
   int lane_shift = 0;
   while ((1 << lane_shift) < D / 4) ++lane_shift;      // D <= 256 -> at most 64 lanes per row
   const unsigned blocks = blocks_for(n_rows << lane_shift);
+  ProfScope prof("merge", s);
   if (o_lowp != nullptr && lowp_dtype == ST_BF16) {
     hipLaunchKernelGGL(merge_kernel<true>, dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part,
                        n_rows, Sq, Hq, D / 4, lane_shift, (uint2*)o_lowp);
@@ -169,6 +170,7 @@ hipError_t launch_delta(const View& d_o, int d_o_dtype, const View& o, int o_dty
   if (n_rows == 0) return hipSuccess;
   const dim3 grid(blocks_for(n_rows * 16)), block(256);
   const bool db = d_o_dtype == ST_BF16, ob = o_dtype == ST_BF16;
+  ProfScope prof("delta", s);
   if (db && ob) hipLaunchKernelGGL((delta_kernel<true, true>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
   else if (db) hipLaunchKernelGGL((delta_kernel<true, false>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
   else if (ob) hipLaunchKernelGGL((delta_kernel<false, true>), grid, block, 0, s, d_o, o, delta, B, Sq, Hq, D);
@@ -181,6 +183,7 @@ hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hi
   if (dst_dtype == ST_F32) return hipMemcpyAsync(dst, src, n * sizeof(float), hipMemcpyDeviceToDevice, s);
   const int64_t n_vec = n / 4;
   const int tail = (int)(n - n_vec * 4);
+  ProfScope prof("cast", s);
   hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n_vec + tail)), dim3(256), 0, s, (const float4*)src,
                      (uint2*)dst, n_vec, src + n_vec * 4, (uint16_t*)dst + n_vec * 4, tail);
   return hipGetLastError();

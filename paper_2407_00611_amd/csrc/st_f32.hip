@@ -234,16 +234,21 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_dkv_f32_kernel(const BwdArgs 
 
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t stream) {
   const dim3 grid((a.s.Sq + kWaves - 1) / kWaves, a.s.Hq, a.s.B);
+  ProfScope prof("fwd_f32", stream);
   hipLaunchKernelGGL(fwd_f32_kernel, grid, dim3(kWaves * 64), 0, stream, a);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t stream) {
   const dim3 grid_q((a.s.Sq + kWaves - 1) / kWaves, a.s.Hq, a.s.B);
-  hipLaunchKernelGGL(bwd_dq_f32_kernel, grid_q, dim3(kWaves * 64), 0, stream, a);
+  {
+    ProfScope prof("bwd_dq_f32", stream);
+    hipLaunchKernelGGL(bwd_dq_f32_kernel, grid_q, dim3(kWaves * 64), 0, stream, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.t.n == 0 || a.s.Sk == 0) return e;
   const dim3 grid_k((a.s.Sk + kWaves - 1) / kWaves, a.s.Hkv, a.s.B * a.t.n);
+  ProfScope prof("bwd_dkv_f32", stream);
   hipLaunchKernelGGL(bwd_dkv_f32_kernel, grid_k, dim3(kWaves * 64), 0, stream, a);
   return hipGetLastError();
 }

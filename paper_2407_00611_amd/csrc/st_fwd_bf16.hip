@@ -298,6 +298,7 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
   const int64_t total = (int64_t)n_qt * a.s.Hq * a.s.B;
   if (total <= 0) return hipSuccess;
   if (total > 0x7fffffff) return hipErrorInvalidValue;
+  ProfScope prof("fwd_bf16", stream);
   if (a.s.D == 128) hipLaunchKernelGGL(fwd_bf16_kernel<128>, dim3((unsigned)total), dim3(256), 0, stream, a);
   else if (a.s.D == 64) hipLaunchKernelGGL(fwd_bf16_kernel<64>, dim3((unsigned)total), dim3(256), 0, stream, a);
   else return hipErrorInvalidValue;

@@ -52,6 +52,15 @@ struct BwdArgs {
   float* dv[kMaxTable];
 };
 
+// Optional per-kernel timing (st_profile_begin / st_profile_end): while enabled, a ProfScope
+// records a HIP event on the launch stream before and after the kernel it brackets.
+struct ProfScope {
+  ProfScope(const char* name, hipStream_t s);
+  ~ProfScope();
+  int slot;
+  hipStream_t stream;
+};
+
 // ---- launchers (each returns hipGetLastError() after the launch) ----
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);

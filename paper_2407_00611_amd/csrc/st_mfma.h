@@ -79,6 +79,80 @@ __device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
   return (4 * g + (s >> 2)) * stride + (16 * half + 4 * (s & 3)) * 2;
 }
 
+// ---- XOR-swizzled LDS tiles -------------------------------------------------------------------
+// A tile of ROWS x D bf16 is stored row-major without padding (D*2 bytes per row) in 16-byte
+// chunks; chunk c of row r lives at chunk position c ^ f(r).  f is chosen so that both access
+// patterns of the MFMA operands are bank-conflict free:
+//   * 16-byte reads of one chunk column by 16 consecutive rows (A/B operand, k along D)
+//   * transpose reads of 4 consecutive rows x 64 contiguous bytes (A operand of the transposed tile)
+template <int D>
+__device__ __forceinline__ int swz(int row, int chunk) {
+  const int f = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+  return row * (D * 2) + ((chunk ^ f) << 4);
+}
+
+// operand fragment with k along D: row (row0 + l % 32), elements 16 ks + 8 g .. + 7
+template <int D>
+__device__ __forceinline__ bf16x8 lds_frag(const ST_LDS char* tile, int row0, int ks, int lane) {
+  return lds_read_b128(tile + swz<D>(row0 + (lane & 31), 2 * ks + (lane >> 5)));
+}
+
+// A-operand fragment of the TRANSPOSED tile: column (col0 + l % 32) at rows
+// row0 + 4g + {0..3} and row0 + 8 + 4g + {0..3} (the slot order of pack_c_as_b); row0 % 16 == 0, col0 % 32 == 0
+template <int D>
+__device__ __forceinline__ bf16x8 lds_frag_tr(const ST_LDS char* tile, int row0, int col0, int lane) {
+  const int g = lane >> 5, s = lane & 15, half = (lane >> 4) & 1;
+  const int row = row0 + 4 * g + (s >> 2);
+  const int chunk = col0 / 8 + 2 * half + ((s & 3) >> 1);
+  const int sub = (s & 1) * 8;
+  u32x2 lo = lds_read_tr16(tile + swz<D>(row, chunk) + sub);
+  u32x2 hi = lds_read_tr16(tile + swz<D>(row + 8, chunk) + sub);
+  u32x4 u = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// global -> registers -> swizzled LDS staging of a ROWS x D bf16 tile by 256 threads.
+// Rows at or beyond row_limit read as zero (no out-of-bounds access).
+template <int D, int ROWS>
+struct StageRegs {
+  static constexpr int kN = ROWS * (D / 8) / 256;
+  static_assert(kN >= 1 && ROWS * (D / 8) % 256 == 0, "tile must split evenly over 256 threads");
+  u32x4 x[kN];
+};
+
+template <int D, int ROWS>
+__device__ __forceinline__ void stage_load(StageRegs<D, ROWS>& r, const char* base, int64_t row_stride_elems,
+                                           int row0, int row_limit, int tid) {
+  constexpr int PPR = D / 8;
+#pragma unroll
+  for (int j = 0; j < StageRegs<D, ROWS>::kN; ++j) {
+    const int p = tid + 256 * j;
+    const int row = p / PPR, chunk = p % PPR;
+    if (row0 + row < row_limit)
+      r.x[j] = *reinterpret_cast<const u32x4*>(base + ((int64_t)(row0 + row) * row_stride_elems + chunk * 8) * 2);
+    else
+      r.x[j] = u32x4{0, 0, 0, 0};
+  }
+}
+
+template <int D, int ROWS>
+__device__ __forceinline__ void stage_store(const StageRegs<D, ROWS>& r, ST_LDS char* tile, int tid) {
+  constexpr int PPR = D / 8;
+#pragma unroll
+  for (int j = 0; j < StageRegs<D, ROWS>::kN; ++j) {
+    const int p = tid + 256 * j;
+    *reinterpret_cast<ST_LDS u32x4*>(tile + swz<D>(p / PPR, p % PPR)) = r.x[j];
+  }
+}
+
+// operand fragment straight from global memory: row `row` (zero if row >= row_limit), elements 16 ks + 8 g .. + 7
+__device__ __forceinline__ bf16x8 global_frag(const char* base, int64_t row_stride_elems, int row, int row_limit,
+                                              int ks, int g) {
+  if (row < row_limit)
+    return *reinterpret_cast<const bf16x8*>(base + ((int64_t)row * row_stride_elems + 16 * ks + 8 * g) * 2);
+  return __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+}
+
 __device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
 __device__ __forceinline__ float xhalf_sum(float x) { return x + __shfl_xor(x, 32); }
 

@@ -1,0 +1,109 @@
+"""GPU parity, bf16 backward (MFMA path) against the fp64 oracle on the bf16-rounded inputs.
+Tolerance: max abs 2e-2 and relative Frobenius 1e-2 per tensor."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_00611_amd as st
+import synth_inputs as si
+from oracle import attention as oa
+from util import assert_close, host, positions, upload
+
+pytestmark = pytest.mark.gpu
+
+STEP_CASES = [
+    # name, B, Hq, Hkv, D, Sq, Sk, n, q_offset, causal
+    ("ragged_causal_gqa_d128", 2, 4, 2, 128, 300, 200, 3, 600 - 300, True),
+    ("noncausal_d128", 1, 2, 2, 128, 70, 130, 2, 0, False),
+    ("future_rows_d128", 1, 2, 1, 128, 100, 90, 2, -37, True),
+    ("ragged_causal_d64", 2, 3, 1, 64, 260, 150, 2, 40, True),
+    ("noncausal_d64", 1, 4, 4, 64, 515, 64, 3, 0, False),
+    ("one_row_one_key", 1, 1, 1, 128, 1, 1, 1, 0, True),
+    ("wide_kv_tile", 1, 2, 1, 128, 130, 600, 1, 450, True),
+]
+
+
+def _workload(c):
+    name, B, Hq, Hkv, D, Sq, Sk, n, q0, causal = c
+    return si.Workload(name, 90 + len(name), "bf16", B, Hq, Hkv, D, Sq, Sk, n, q0, causal, True)
+
+
+@pytest.mark.parametrize("case", STEP_CASES, ids=[c[0] for c in STEP_CASES])
+def test_delta_and_block_bwd_steps(case):
+    w = _workload(case)
+    inp = si.make_inputs(w)
+    q, ks, vs, d_o = upload(inp)
+    q_pos, k_pos = positions(w)
+    # final statistics from the oracle, so that this test isolates the backward step
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    o_dev = torch.from_numpy(o_ref.astype(np.float32)).cuda()
+    lse_dev = torch.from_numpy(lse_ref.astype(np.float32)).cuda()
+    delta = st.st_attn_delta(d_o, o_dev)
+    delta_ref = oa.delta(inp.d_o, o_ref)
+    assert_close(host(delta), delta_ref, "bf16", "delta")
+    o_bf = o_dev.to(torch.bfloat16)                                     # O saved in the storage dtype
+    delta_bf = st.st_attn_delta(d_o, o_bf)
+    assert_close(host(delta_bf), oa.delta(inp.d_o, host(o_bf)), "bf16", "delta from bf16 O")
+
+    dq = torch.zeros((w.B, w.Sq, w.Hq, w.D), device="cuda")
+    dq_ref = np.zeros(o_ref.shape)
+    lse_f, delta_f = host(lse_dev), host(delta)
+    for j in range(w.n_chunks):
+        print(f"[{w.name}] block_bwd chunk {j}", flush=True)
+        dk = torch.zeros((w.B, w.Sk, w.Hkv, w.D), device="cuda")
+        dv = torch.zeros_like(dk)
+        st.st_attn_block_bwd(q, ks[j], vs[j], d_o, lse_dev, delta, w.q_offset, w.k_offset(j), w.causal, w.scale,
+                             dq, dk, dv)
+        dq_j, dk_r, dv_r = oa.block_backward(inp.q, inp.k[j], inp.v[j], inp.d_o, lse_f, delta_f, q_pos, k_pos[j],
+                                             w.causal, w.scale)
+        dq_ref += dq_j
+        assert_close(host(dk), dk_r, "bf16", f"dk[{j}]")
+        assert_close(host(dv), dv_r, "bf16", f"dv[{j}]")
+    assert_close(host(dq), dq_ref, "bf16", "dq (steps)")
+    dq_m, _, _ = oa.attention_backward(inp.q, inp.k, inp.v, inp.d_o, q_pos, k_pos, w.causal, w.scale)
+    assert_close(host(dq), dq_m, "bf16", "dq vs monolithic")
+
+
+def _ring_fwd_bwd(w, order, members, mode):
+    inp = si.make_inputs(w)
+    q, ks, vs, d_o = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, mode)
+    dq = torch.zeros_like(o)
+    dk = [torch.zeros(k.shape, device="cuda") for k in ks]
+    dv = [torch.zeros(k.shape, device="cuda") for k in ks]
+    st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv, mode)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    dq_r, dk_r, dv_r = oa.attention_backward(inp.q, inp.k, inp.v, inp.d_o, q_pos, k_pos, w.causal, w.scale)
+    assert_close(host(o), o_ref, "bf16", "o")
+    assert_close(host(lse), lse_ref, "bf16", "lse", lse=True)
+    assert_close(host(dq), dq_r, "bf16", "dq")
+    assert_close(host(st.st_cast_from_f32(dq, st.ST_BF16)), dq_r, "bf16", "dq bf16")
+    for j in range(w.n_chunks):
+        assert_close(host(dk[j]), dk_r[j], "bf16", f"dk[{j}]")
+        assert_close(host(dv[j]), dv_r[j], "bf16", f"dv[{j}]")
+    return dq, dk, dv
+
+
+@pytest.mark.parametrize("mode", [st.ST_RING_STEPWISE, st.ST_RING_FUSED], ids=["stepwise", "fused"])
+@pytest.mark.parametrize("D", [128, 64])
+def test_ring_fwd_bwd_small(mode, D):
+    w = si.Workload("ring_bf16_small", 95, "bf16", 1, 4, 2, D, 200, 200, 8, 5 * 200, True, True)
+    for C in (1, 2):
+        order, members = st.st_visit_order(8, C, 5)
+        print(f"[ring small D={D}] mode {mode} C={C}", flush=True)
+        _ring_fwd_bwd(w, order, members, mode)
+
+
+def test_backward_is_bit_reproducible():
+    w = si.Workload("ring_bf16_repro", 96, "bf16", 1, 4, 1, 128, 300, 300, 4, 900, True, True)
+    a = _ring_fwd_bwd(w, [0, 1, 2, 3], None, st.ST_RING_FUSED)
+    b = _ring_fwd_bwd(w, [0, 1, 2, 3], None, st.ST_RING_FUSED)
+    assert torch.equal(a[0], b[0])
+    for j in range(4):
+        assert torch.equal(a[1][j], b[1][j]) and torch.equal(a[2][j], b[2][j])
+    # another visit order changes the forward's rounding (hence lse and Delta), so the gradients
+    # agree with the oracle (checked inside the helper) but not bit for bit
+    _ring_fwd_bwd(w, [3, 1, 0, 2], [0, 1, 0, 1], st.ST_RING_FUSED)

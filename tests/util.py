@@ -48,7 +48,10 @@ def positions(w: si.Workload):
 def assert_close(x, ref, dtype: str, what: str = "", lse: bool = False):
     """fp32 path: ||x-ref||_F <= 1e-5 ||ref||_F and max|x-ref| <= 1e-5 max|ref|.
     bf16 path: max|x-ref| <= 2e-2 and ||x-ref||_F <= 1e-2 ||ref||_F.
-    -inf entries (empty rows of an lse) must match exactly."""
+    -inf entries (empty rows of an lse) must match exactly.
+    The Frobenius bound carries an absolute floor of 1e-6 RMS (bf16 path) / 1e-9 RMS (fp32 path):
+    where the exact result cancels to (almost) zero, e.g. dS = P (dP - Delta) with a single visible
+    key, what is left is fp32 rounding of O(1) intermediates and a relative bound is meaningless."""
     x = np.asarray(x, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert x.shape == ref.shape, f"{what}: shape {x.shape} vs {ref.shape}"
@@ -61,10 +64,10 @@ def assert_close(x, ref, dtype: str, what: str = "", lse: bool = False):
     fro_ref = np.linalg.norm(ref)
     fro = np.linalg.norm(x - ref)
     if dtype == "f32":
-        assert fro <= 1e-5 * fro_ref + 1e-30, f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-5"
-        assert err.max(initial=0.0) <= 1e-5 * np.abs(ref).max(initial=0.0) + 1e-30, \
+        assert fro <= 1e-5 * fro_ref + 1e-9 * np.sqrt(x.size), f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-5"
+        assert err.max(initial=0.0) <= 1e-5 * np.abs(ref).max(initial=0.0) + 1e-9, \
             f"{what}: max err {err.max():.3e} vs max|ref| {np.abs(ref).max():.3e}"
     else:
         assert err.max(initial=0.0) <= 2e-2, f"{what}: max abs err {err.max():.3e} > 2e-2"
         if not lse:
-            assert fro <= 1e-2 * fro_ref + 1e-30, f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-2"
+            assert fro <= 1e-2 * fro_ref + 1e-6 * np.sqrt(x.size), f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-2"
