@@ -30,12 +30,18 @@ __device__ __forceinline__ int visible_keys(int causal, int Sk, int64_t qpos, in
 // =============================================================================================
 // dQ kernel
 // =============================================================================================
+#ifndef ST_DQ_WQ
+#define ST_DQ_WQ 64
+#endif
+#ifndef ST_DKV_WK
+#define ST_DKV_WK 64
+#endif
 constexpr int kQ_BN = 64;        // keys per staged tile
-constexpr int kQ_WQ = 64;        // queries per wavefront
+constexpr int kQ_WQ = ST_DQ_WQ;  // queries per wavefront (32: two workgroups per CU)
 constexpr int kQ_BM = 4 * kQ_WQ;
 
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_dq_bf16_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(const BwdArgs a) {
   constexpr int QB = kQ_WQ / 32, KB = kQ_BN / 32, KS = D / 16, DB = D / 32;
   constexpr int kTile = kQ_BN * D * 2;           // bytes of one K (or V) tile
   __shared__ __attribute__((aligned(16))) char smem_raw[4 * kTile];   // 2 stages x (K, V)
@@ -214,12 +220,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_bf16_kernel(const BwdArgs a) {
 // =============================================================================================
 // dK / dV kernel
 // =============================================================================================
-constexpr int kK_WK = 64;         // keys per wavefront
+constexpr int kK_WK = ST_DKV_WK;  // keys per wavefront (32: two workgroups per CU)
 constexpr int kK_BK = 4 * kK_WK;  // keys per workgroup
-constexpr int kK_BQ = 64;         // queries per staged tile
+constexpr int kK_BQ = ST_DKV_WK == 32 ? 32 : 64;   // queries per staged tile
 
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(256, kK_WK == 32 ? 2 : 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   constexpr int NB = kK_WK / 32;   // 32-key blocks per wavefront
   constexpr int QB = kK_BQ / 32;   // 32-query blocks per staged tile
   constexpr int KS = D / 16, DB = D / 32;

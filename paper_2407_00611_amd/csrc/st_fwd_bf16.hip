@@ -17,8 +17,9 @@ namespace st {
 namespace {
 
 constexpr int kBN = 64;       // keys per tile
-constexpr int kWQ = 64;       // queries per wavefront
-constexpr int kBM = 4 * kWQ;  // queries per workgroup
+#ifndef ST_FWD_WQ
+#define ST_FWD_WQ 32
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int D>
@@ -78,8 +79,11 @@ __device__ __forceinline__ int visible_keys(int causal, int Sk, int64_t qpos, in
   return n < 0 ? 0 : (n > Sk ? Sk : (int)n);
 }
 
-template <int D>
-__global__ __launch_bounds__(256, 1) void fwd_bf16_kernel(const FwdArgs a) {
+// kWQ = queries per wavefront: 64 (one wavefront per SIMD) or 32 (two workgroups per CU, so that one
+// wavefront's softmax overlaps another's MFMAs)
+template <int D, int kWQ>
+__global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const FwdArgs a) {
+  constexpr int kBM = 4 * kWQ;   // queries per workgroup
   constexpr int QB = kWQ / 32;   // 32-query blocks per wavefront
   constexpr int KB = kBN / 32;   // 32-key blocks per tile
   constexpr int KS = D / 16;     // contraction steps of S^T = K Q^T
@@ -102,7 +106,6 @@ __global__ __launch_bounds__(256, 1) void fwd_bf16_kernel(const FwdArgs a) {
   // ---- Q fragments (B operand of S^T): query column r of block qb, d = 16 ks + 8 g .. +7
   const int q_row0 = qt * kBM + wave * kWQ;
   bf16x8 qf[QB][KS];
-  int nvis_row[QB];     // filled per chunk
   int64_t qpos[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -294,13 +297,15 @@ __global__ __launch_bounds__(256, 1) void fwd_bf16_kernel(const FwdArgs a) {
 }  // namespace
 
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
+  constexpr int kWQ = ST_FWD_WQ;
+  constexpr int kBM = 4 * kWQ;
   const int n_qt = (a.s.Sq + kBM - 1) / kBM;
   const int64_t total = (int64_t)n_qt * a.s.Hq * a.s.B;
   if (total <= 0) return hipSuccess;
   if (total > 0x7fffffff) return hipErrorInvalidValue;
   ProfScope prof("fwd_bf16", stream);
-  if (a.s.D == 128) hipLaunchKernelGGL(fwd_bf16_kernel<128>, dim3((unsigned)total), dim3(256), 0, stream, a);
-  else if (a.s.D == 64) hipLaunchKernelGGL(fwd_bf16_kernel<64>, dim3((unsigned)total), dim3(256), 0, stream, a);
+  if (a.s.D == 128) hipLaunchKernelGGL((fwd_bf16_kernel<128, kWQ>), dim3((unsigned)total), dim3(256), 0, stream, a);
+  else if (a.s.D == 64) hipLaunchKernelGGL((fwd_bf16_kernel<64, kWQ>), dim3((unsigned)total), dim3(256), 0, stream, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
