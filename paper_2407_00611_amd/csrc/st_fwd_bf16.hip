@@ -9,7 +9,10 @@
 //   online softmax in the C layout: a lane owns ONE query column, so the row statistics are
 //                      per-lane scalars and only one cross-half exchange per tile is needed
 //   O^T += V^T P^T     A = V^T fragment (LDS transpose reads), B = P^T straight from the S registers
-// K/V tiles are staged global -> registers -> LDS, double buffered, one barrier per tile.
+// K/V tiles go global -> LDS directly (XOR-swizzled, double buffered), one barrier per tile.
+#include <cstdlib>
+#include <type_traits>
+
 #include "st_internal.h"
 #include "st_mfma.h"
 
@@ -21,56 +24,7 @@ constexpr int kBN = 64;       // keys per tile
 #define ST_FWD_WQ 32
 #endif
 constexpr float kLog2e = 1.4426950408889634f;
-
-template <int D>
-struct FwdSmem {
-  static constexpr int kKStr = D * 2 + 16;   // bytes per K row: consecutive rows shift by 4 banks
-  static constexpr int kVStr = D * 2 + 64;   // bytes per V row: transposed reads touch 4 rows x 64 B
-  static constexpr int kKBytes = kBN * kKStr;
-  static constexpr int kVBytes = kBN * kVStr;
-  static constexpr int kStage = kKBytes + kVBytes;
-  static constexpr int kTotal = 2 * kStage;
-};
-
-// global -> register staging of one 64-key K and V tile: 16-byte pieces, consecutive lanes on
-// consecutive pieces of a row; rows beyond the chunk read as zero (never out of bounds)
-template <int D>
-struct TileRegs {
-  static constexpr int kPiecesPerRow = D / 8;
-  static constexpr int kPerThread = kBN * kPiecesPerRow / 256;
-  u32x4 k[kPerThread], v[kPerThread];
-};
-
-template <int D>
-__device__ __forceinline__ void load_tile(TileRegs<D>& r, const char* kbase, const char* vbase, int64_t kss,
-                                          int64_t vss, int t0, int Sk, int tid) {
-  constexpr int PPR = TileRegs<D>::kPiecesPerRow;
-#pragma unroll
-  for (int j = 0; j < TileRegs<D>::kPerThread; ++j) {
-    const int p = tid + 256 * j;
-    const int row = p / PPR, col = p % PPR;
-    const int t = t0 + row;
-    if (t < Sk) {
-      r.k[j] = *reinterpret_cast<const u32x4*>(kbase + ((int64_t)t * kss + col * 8) * 2);
-      r.v[j] = *reinterpret_cast<const u32x4*>(vbase + ((int64_t)t * vss + col * 8) * 2);
-    } else {
-      r.k[j] = u32x4{0, 0, 0, 0};
-      r.v[j] = u32x4{0, 0, 0, 0};
-    }
-  }
-}
-
-template <int D>
-__device__ __forceinline__ void store_tile(const TileRegs<D>& r, ST_LDS char* stage, int tid) {
-  constexpr int PPR = TileRegs<D>::kPiecesPerRow;
-#pragma unroll
-  for (int j = 0; j < TileRegs<D>::kPerThread; ++j) {
-    const int p = tid + 256 * j;
-    const int row = p / PPR, col = p % PPR;
-    *reinterpret_cast<ST_LDS u32x4*>(stage + row * FwdSmem<D>::kKStr + col * 16) = r.k[j];
-    *reinterpret_cast<ST_LDS u32x4*>(stage + FwdSmem<D>::kKBytes + row * FwdSmem<D>::kVStr + col * 16) = r.v[j];
-  }
-}
+constexpr float kRescaleGap = 8.f;   // log2 units
 
 // visible prefix of a chunk for a query at global position qpos
 __device__ __forceinline__ int visible_keys(int causal, int Sk, int64_t qpos, int64_t k0) {
@@ -88,8 +42,8 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   constexpr int KB = kBN / 32;   // 32-key blocks per tile
   constexpr int KS = D / 16;     // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;     // 32-row blocks of O^T
-  using SM = FwdSmem<D>;
-  __shared__ __attribute__((aligned(16))) char smem_raw[SM::kTotal];
+  constexpr int kTile = kBN * D * 2;          // bytes of one K (or V) tile, XOR-swizzled, unpadded
+  __shared__ __attribute__((aligned(1024))) char smem_raw[4 * kTile];   // 2 stages x (K, V)
   ST_LDS char* smem = (ST_LDS char*)smem_raw;
 
   const Shape& s = a.s;
@@ -139,7 +93,6 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     l_run[qb] = 0.f;
   }
   const float c_exp = s.scale * kLog2e;
-  const int tr_off = tr_lane_offset(lane, SM::kVStr);
 
   // ---- flattened (chunk, tile) walk with one-tile lookahead
   // number of tiles the workgroup needs from chunk c: up to the last key its last row may see
@@ -150,18 +103,15 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   int c_cur = 0, t_cur = 0, n_cur = 0;          // current chunk, tile, tiles in chunk
   while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) == 0) ++c_cur;
 
-  TileRegs<D> stage_regs;
-  auto issue_load = [&](int c, int t) {
+  auto issue_load = [&](int c, int t, int stage) {
     const char* kb = (const char*)a.t.k[c] + ((int64_t)b * a.t.ksb + (int64_t)hk * a.t.ksh) * 2;
     const char* vb = (const char*)a.t.v[c] + ((int64_t)b * a.t.vsb + (int64_t)hk * a.t.vsh) * 2;
-    load_tile<D>(stage_regs, kb, vb, a.t.kss, a.t.vss, t * kBN, s.Sk, tid);
+    stage_dma<D, kBN>(kb, a.t.kss, t * kBN, s.Sk, smem + stage * 2 * kTile, tid);
+    stage_dma<D, kBN>(vb, a.t.vss, t * kBN, s.Sk, smem + stage * 2 * kTile + kTile, tid);
   };
 
   int buf = 0;
-  if (c_cur < a.t.n) {
-    issue_load(c_cur, 0);
-    store_tile<D>(stage_regs, smem, tid);
-  }
+  if (c_cur < a.t.n) issue_load(c_cur, 0, 0);
   __syncthreads();
 
   while (c_cur < a.t.n) {
@@ -173,17 +123,16 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
       while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) == 0) ++c_nxt;
     }
     const bool have_next = c_nxt < a.t.n;
-    if (have_next) issue_load(c_nxt, t_nxt);
+    if (have_next) issue_load(c_nxt, t_nxt, buf ^ 1);
 
     // ---- compute on the staged tile
     const int64_t k0 = a.t.k_offset[c_cur];
     const int tile_k0 = t_cur * kBN;
     // visible-prefix lengths: first / last live row of the wavefront and this lane's rows
     const int nv_wave_min = visible_keys(s.causal, s.Sk, s.q_offset + wave_first_row, k0);
-    const int nv_wave_max = wave_live ? visible_keys(s.causal, s.Sk, s.q_offset + wave_last_row, k0) : 0;
-    if (tile_k0 < nv_wave_max) {                     // wave-uniform: some row of the wavefront sees this tile
-      const ST_LDS char* ktile = smem + buf * SM::kStage;
-      const ST_LDS char* vtile = ktile + SM::kKBytes;
+    {  // every wavefront computes every tile the workgroup walks; rows that see nothing of it are masked
+      const ST_LDS char* ktile = smem + buf * 2 * kTile;
+      const ST_LDS char* vtile = ktile + kTile;
       f32x16 sc[KB][QB];
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
@@ -195,12 +144,14 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
       for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-          const bf16x8 kf = lds_read_b128(ktile + (32 * kb + r) * SM::kKStr + (16 * ks + 8 * g) * 2);
+          const bf16x8 kf = lds_frag<D>(ktile, 32 * kb, ks, lane);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) sc[kb][qb] = mfma32(kf, qf[qb][ks], sc[kb][qb]);
         }
 
       const bool need_mask = tile_k0 + kBN > nv_wave_min;     // wave-uniform
+      float mx[QB];
+      bool jump = false;
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         if (need_mask) {
@@ -213,51 +164,67 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
               if (key >= nv) sc[kb][qb][v] = -INFINITY;
             }
         }
-        float mx = sc[0][qb][0];
+        float x = sc[0][qb][0];
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc[kb][qb][v]);
-        mx = xhalf_max(mx);
-        const float m_new = fmaxf(m_run[qb], mx);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_use) * c_exp);
-        const float mc = m_use * c_exp;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(sc[kb][qb][v], c_exp, -mc));
-            sc[kb][qb][v] = p;
-            psum += p;
-          }
-        l_run[qb] = l_run[qb] * alpha + psum;
-        m_run[qb] = m_new;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc_o[db][qb][v] *= alpha;
+          for (int v = 0; v < 16; ++v) x = fmaxf(x, sc[kb][qb][v]);
+        mx[qb] = xhalf_max(x);
+        jump = jump || (mx[qb] - m_run[qb]) * c_exp > kRescaleGap || (m_run[qb] == -INFINITY && mx[qb] != -INFINITY);
       }
 
-      // O^T += V^T P^T : contraction over the tile's keys in steps of 16 (kb, m)
+      // Lazy rescale: the exponent reference m_run only moves when some row's tile maximum exceeds it
+      // by more than kRescaleGap (log2 units), so p <= 2^kRescaleGap and the O accumulator is rescaled
+      // rarely.  Exact in real arithmetic: O and l stay consistent with whatever reference is in use,
+      // and lse = m_run * scale + ln(l) at the end.  The rest of the tile exists twice (with and
+      // without the rescale) so that the common path carries the accumulators through untouched.
+      auto rescale_rows = [&]() {
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
+        for (int qb = 0; qb < QB; ++qb) {
+          const float m_new = fmaxf(m_run[qb], mx[qb]);
+          const float m_use = m_new == -INFINITY ? 0.f : m_new;
+          const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_use) * c_exp);
+          l_run[qb] *= alpha;
+          m_run[qb] = m_new;
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-          bf16x8 pf[QB];
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) pf[qb] = pack_c_as_b(sc[kb][qb], m);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const bf16x8 vf = lds_read_tr_frag(vtile, 32 * kb + 16 * m, 32 * db, SM::kVStr, tr_off);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) acc_o[db][qb] = mfma32(vf, pf[qb], acc_o[db][qb]);
-          }
+          for (int db = 0; db < DB; ++db) scale_in_place(acc_o[db][qb], alpha);
         }
+      };
+      auto finish_tile = [&]() {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          const float mc = (m_run[qb] == -INFINITY ? 0.f : m_run[qb]) * c_exp;
+          float psum = 0.f;
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const float p = __builtin_amdgcn_exp2f(fmaf(sc[kb][qb][v], c_exp, -mc));
+              sc[kb][qb][v] = p;
+              psum += p;
+            }
+          l_run[qb] += psum;
+        }
+        // O^T += V^T P^T : contraction over the tile's keys in steps of 16 (kb, m)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int m = 0; m < 2; ++m) {
+            bf16x8 pf[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) pf[qb] = pack_c_as_b(sc[kb][qb], m);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+              const bf16x8 vf = lds_frag_tr<D>(vtile, 32 * kb + 16 * m, 32 * db, lane);
+#pragma unroll
+              for (int qb = 0; qb < QB; ++qb) acc_o[db][qb] = mfma32(vf, pf[qb], acc_o[db][qb]);
+            }
+          }
+      };
+      if (__builtin_expect(__any(jump), 0)) rescale_rows();
+      finish_tile();
     }
 
-    if (have_next) store_tile<D>(stage_regs, smem + (buf ^ 1) * SM::kStage, tid);
     __syncthreads();
     buf ^= 1;
     c_cur = c_nxt;
@@ -296,8 +263,8 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
 
 }  // namespace
 
-hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
-  constexpr int kWQ = ST_FWD_WQ;
+template <int kWQ>
+hipError_t launch_fwd_bf16_wq(const FwdArgs& a, hipStream_t stream) {
   constexpr int kBM = 4 * kWQ;
   const int n_qt = (a.s.Sq + kBM - 1) / kBM;
   const int64_t total = (int64_t)n_qt * a.s.Hq * a.s.B;
@@ -308,6 +275,15 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
   else if (a.s.D == 64) hipLaunchKernelGGL((fwd_bf16_kernel<64, kWQ>), dim3((unsigned)total), dim3(256), 0, stream, a);
   else return hipErrorInvalidValue;
   return hipGetLastError();
+}
+
+hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
+  // tuning override: ST_FWD_WQ=64 selects one wavefront per SIMD with 64 queries each
+  static const int wq = [] {
+    const char* e = getenv("ST_FWD_WQ");
+    return e ? atoi(e) : ST_FWD_WQ;
+  }();
+  return wq == 64 ? launch_fwd_bf16_wq<64>(a, stream) : launch_fwd_bf16_wq<32>(a, stream);
 }
 
 }  // namespace st

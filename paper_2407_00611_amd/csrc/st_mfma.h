@@ -145,12 +145,62 @@ __device__ __forceinline__ void stage_store(const StageRegs<D, ROWS>& r, ST_LDS 
   }
 }
 
+// Direct global -> LDS staging (no staging registers, no LDS write instructions): one wavefront-wide
+// global_load_lds_dwordx4 moves 64 x 16 bytes to 1 KiB of consecutive LDS, lane L to byte 16 L.  The
+// swizzle is therefore applied on the global side: the lane that fills chunk position pc of a row
+// fetches chunk pc ^ f(row).  Rows at or beyond row_limit (>= 1) re-read row row_limit - 1; every
+// consumer masks such rows, so only finiteness of their contents matters.  The caller must wait
+// (s_waitcnt vmcnt(0), which the compiler places before the workgroup barrier) before reading.
+typedef __attribute__((address_space(1))) const void* st_global_ptr;
+typedef __attribute__((address_space(3))) void* st_lds_ptr;
+
+template <int D, int ROWS>
+__device__ __forceinline__ void stage_dma(const char* base, int64_t row_stride_elems, int row0, int row_limit,
+                                          ST_LDS char* tile, int tid) {
+  constexpr int PPR = D / 8;                 // 16-byte chunks per row
+  constexpr int RPI = 64 / PPR;              // rows per instruction
+  constexpr int PER_WAVE = ROWS / RPI / 4;   // instructions per wavefront (4 wavefronts)
+  static_assert(ROWS % (RPI * 4) == 0, "tile must split evenly over 4 wavefronts");
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int j = 0; j < PER_WAVE; ++j) {
+    const int instr = j * 4 + wave;
+    const int row = instr * RPI + lane / PPR;
+    const int pc = lane % PPR;
+    const int f = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    int grow = row0 + row;
+    grow = grow < row_limit ? grow : row_limit - 1;
+    const char* src = base + ((int64_t)grow * row_stride_elems + (pc ^ f) * 8) * 2;
+    __builtin_amdgcn_global_load_lds((st_global_ptr)src, (st_lds_ptr)(tile + instr * 1024), 16, 0, 0);
+  }
+}
+
 // operand fragment straight from global memory: row `row` (zero if row >= row_limit), elements 16 ks + 8 g .. + 7
 __device__ __forceinline__ bf16x8 global_frag(const char* base, int64_t row_stride_elems, int row, int row_limit,
                                               int ks, int g) {
   if (row < row_limit)
     return *reinterpret_cast<const bf16x8*>(base + ((int64_t)row * row_stride_elems + 16 * ks + 8 * g) * 2);
   return __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+}
+
+// x *= a in ONE asm statement with all sixteen registers tied in place.  Used on rarely taken
+// paths (accumulator rescale): written as plain C++ the product gets a fresh register tuple and the
+// path that skips the multiply has to copy the whole accumulator.
+__device__ __forceinline__ void scale_in_place(f32x16& x, float a) {
+  float x0 = x[0], x1 = x[1], x2 = x[2], x3 = x[3], x4 = x[4], x5 = x[5], x6 = x[6], x7 = x[7];
+  float x8 = x[8], x9 = x[9], xa = x[10], xb = x[11], xc = x[12], xd = x[13], xe = x[14], xf = x[15];
+  // the leading s_nop covers the wait states a transcendental result (a) needs before a VALU use;
+  // the compiler does not insert them for operands of an asm statement
+  asm volatile(
+      "s_nop 4\n\t"
+      "v_mul_f32 %0, %16, %0\n\tv_mul_f32 %1, %16, %1\n\tv_mul_f32 %2, %16, %2\n\tv_mul_f32 %3, %16, %3\n\t"
+      "v_mul_f32 %4, %16, %4\n\tv_mul_f32 %5, %16, %5\n\tv_mul_f32 %6, %16, %6\n\tv_mul_f32 %7, %16, %7\n\t"
+      "v_mul_f32 %8, %16, %8\n\tv_mul_f32 %9, %16, %9\n\tv_mul_f32 %10, %16, %10\n\tv_mul_f32 %11, %16, %11\n\t"
+      "v_mul_f32 %12, %16, %12\n\tv_mul_f32 %13, %16, %13\n\tv_mul_f32 %14, %16, %14\n\tv_mul_f32 %15, %16, %15"
+      : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7), "+v"(x8), "+v"(x9),
+        "+v"(xa), "+v"(xb), "+v"(xc), "+v"(xd), "+v"(xe), "+v"(xf)
+      : "v"(a));
+  x = f32x16{x0, x1, x2, x3, x4, x5, x6, x7, x8, x9, xa, xb, xc, xd, xe, xf};
 }
 
 __device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
