@@ -34,7 +34,7 @@ __device__ __forceinline__ int visible_keys(int causal, int Sk, int64_t qpos, in
 #define ST_DQ_WQ 64
 #endif
 #ifndef ST_DKV_WK
-#define ST_DKV_WK 64
+#define ST_DKV_WK 32
 #endif
 constexpr int kQ_BN = 64;        // keys per staged tile
 constexpr int kQ_WQ = ST_DQ_WQ;  // queries per wavefront (32: two workgroups per CU)
@@ -225,7 +225,7 @@ constexpr int kK_BK = 4 * kK_WK;  // keys per workgroup
 constexpr int kK_BQ = ST_DKV_WK == 32 ? 32 : 64;   // queries per staged tile
 
 template <int D>
-__global__ __launch_bounds__(256, kK_WK == 32 ? 2 : 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   constexpr int NB = kK_WK / 32;   // 32-key blocks per wavefront
   constexpr int QB = kK_BQ / 32;   // 32-query blocks per staged tile
   constexpr int KS = D / 16, DB = D / 32;

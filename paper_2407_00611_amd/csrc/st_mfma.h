@@ -175,6 +175,74 @@ __device__ __forceinline__ void stage_dma(const char* base, int64_t row_stride_e
   }
 }
 
+// The same staging with the DMA written as inline asm: the compiler then does not track it, so it
+// places no vmcnt wait in front of later LDS reads and several tiles can be in flight; the caller
+// waits explicitly (wait_vmcnt<N>: at most N of this wavefront's loads still outstanding).
+__device__ __forceinline__ void dma16_asm(const char* src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(lds_addr), "v"(src) : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+template <int D, int ROWS>
+struct DmaPlan {
+  static constexpr int PPR = D / 8;                 // 16-byte chunks per row
+  static constexpr int RPI = 64 / PPR;              // rows per instruction
+  static constexpr int PER_WAVE = ROWS / RPI / 4;   // instructions per wavefront and tile
+};
+
+template <int D, int ROWS>
+__device__ __forceinline__ void stage_dma_asm(const char* base, int64_t row_stride_elems, int row0, int row_limit,
+                                              uint32_t tile_lds_addr, int tid) {
+  using P = DmaPlan<D, ROWS>;
+  static_assert(ROWS % (P::RPI * 4) == 0, "tile must split evenly over 4 wavefronts");
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#pragma unroll
+  for (int j = 0; j < P::PER_WAVE; ++j) {
+    const int instr = j * 4 + wave;
+    const int row = instr * P::RPI + lane / P::PPR;
+    const int pc = lane % P::PPR;
+    const int f = (D == 128) ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    int grow = row0 + row;
+    grow = grow < row_limit ? grow : row_limit - 1;
+    dma16_asm(base + ((int64_t)grow * row_stride_elems + (pc ^ f) * 8) * 2, tile_lds_addr + instr * 1024);
+  }
+}
+
+// Rarely taken in-place edits of a whole MFMA accumulator tuple (mask, rescale).  They are single asm
+// statements whose only tuple operand is pinned to a[0:15]: with sixteen scalar operands LLVM splits
+// the tuple into scalars around the branch and copies the whole accumulator on the path that skips the
+// edit; with a VGPR constraint the allocator keeps the accumulator in VGPRs for the whole loop and
+// copies it to AGPRs around every MFMA.  The leading wait states cover an MFMA that has just written
+// the tuple and a transcendental that has just produced a scalar input: the compiler inserts no hazard
+// nops in front of the operands of an asm statement.
+
+// x[v] = (cv(v) < lim) ? x[v] : -inf, cv(v) = 8 (v / 4) + v % 4: the C-layout row offset of element v
+// without the lane's 4 g term (the caller folds that and the block base into lim).
+__device__ __forceinline__ void mask_rows_in_place(f32x16& x, int lim) {
+  f32x16 t = x;
+  float t0;
+  const float ninf = -INFINITY;
+#define ST_MASK1(i, cv)                                                                                     \
+  "v_accvgpr_read_b32 %1, a" #i "\n\tv_cmp_gt_i32_e64 vcc, %2, " #cv "\n\ts_nop 1\n\t"                    \
+  "v_cndmask_b32_e32 %1, %3, %1, vcc\n\ts_nop 1\n\tv_accvgpr_write_b32 a" #i ", %1\n\t"
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3\n\t"
+               ST_MASK1(0, 0) ST_MASK1(1, 1) ST_MASK1(2, 2) ST_MASK1(3, 3) ST_MASK1(4, 8) ST_MASK1(5, 9)
+               ST_MASK1(6, 10) ST_MASK1(7, 11) ST_MASK1(8, 16) ST_MASK1(9, 17) ST_MASK1(10, 18) ST_MASK1(11, 19)
+               ST_MASK1(12, 24) ST_MASK1(13, 25) ST_MASK1(14, 26) ST_MASK1(15, 27) "s_nop 3"
+               : "+{a[0:15]}"(t), "=&v"(t0)
+               : "v"(lim), "v"(ninf)
+               : "vcc");
+#undef ST_MASK1
+  x = t;
+}
+
 // operand fragment straight from global memory: row `row` (zero if row >= row_limit), elements 16 ks + 8 g .. + 7
 __device__ __forceinline__ bf16x8 global_frag(const char* base, int64_t row_stride_elems, int row, int row_limit,
                                               int ks, int g) {
@@ -183,24 +251,21 @@ __device__ __forceinline__ bf16x8 global_frag(const char* base, int64_t row_stri
   return __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
 }
 
-// x *= a in ONE asm statement with all sixteen registers tied in place.  Used on rarely taken
-// paths (accumulator rescale): written as plain C++ the product gets a fresh register tuple and the
-// path that skips the multiply has to copy the whole accumulator.
+// x *= a
 __device__ __forceinline__ void scale_in_place(f32x16& x, float a) {
-  float x0 = x[0], x1 = x[1], x2 = x[2], x3 = x[3], x4 = x[4], x5 = x[5], x6 = x[6], x7 = x[7];
-  float x8 = x[8], x9 = x[9], xa = x[10], xb = x[11], xc = x[12], xd = x[13], xe = x[14], xf = x[15];
-  // the leading s_nop covers the wait states a transcendental result (a) needs before a VALU use;
-  // the compiler does not insert them for operands of an asm statement
-  asm volatile(
-      "s_nop 4\n\t"
-      "v_mul_f32 %0, %16, %0\n\tv_mul_f32 %1, %16, %1\n\tv_mul_f32 %2, %16, %2\n\tv_mul_f32 %3, %16, %3\n\t"
-      "v_mul_f32 %4, %16, %4\n\tv_mul_f32 %5, %16, %5\n\tv_mul_f32 %6, %16, %6\n\tv_mul_f32 %7, %16, %7\n\t"
-      "v_mul_f32 %8, %16, %8\n\tv_mul_f32 %9, %16, %9\n\tv_mul_f32 %10, %16, %10\n\tv_mul_f32 %11, %16, %11\n\t"
-      "v_mul_f32 %12, %16, %12\n\tv_mul_f32 %13, %16, %13\n\tv_mul_f32 %14, %16, %14\n\tv_mul_f32 %15, %16, %15"
-      : "+v"(x0), "+v"(x1), "+v"(x2), "+v"(x3), "+v"(x4), "+v"(x5), "+v"(x6), "+v"(x7), "+v"(x8), "+v"(x9),
-        "+v"(xa), "+v"(xb), "+v"(xc), "+v"(xd), "+v"(xe), "+v"(xf)
-      : "v"(a));
-  x = f32x16{x0, x1, x2, x3, x4, x5, x6, x7, x8, x9, xa, xb, xc, xd, xe, xf};
+  f32x16 t = x;
+  float t0, t1;
+#define ST_SC2(i, j)                                                                            \
+  "v_accvgpr_read_b32 %1, a" #i "\n\tv_accvgpr_read_b32 %2, a" #j "\n\ts_nop 1\n\t"           \
+  "v_mul_f32 %1, %3, %1\n\tv_mul_f32 %2, %3, %2\n\ts_nop 1\n\t"                              \
+  "v_accvgpr_write_b32 a" #i ", %1\n\tv_accvgpr_write_b32 a" #j ", %2\n\t"
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3\n\t"
+               ST_SC2(0, 1) ST_SC2(2, 3) ST_SC2(4, 5) ST_SC2(6, 7) ST_SC2(8, 9) ST_SC2(10, 11) ST_SC2(12, 13)
+               ST_SC2(14, 15) "s_nop 3"
+               : "+{a[0:15]}"(t), "=&v"(t0), "=&v"(t1)
+               : "v"(a));
+#undef ST_SC2
+  x = t;
 }
 
 __device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
