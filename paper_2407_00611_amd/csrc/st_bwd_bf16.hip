@@ -340,9 +340,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const int blk_i0 = i0 + 32 * qb;
-      // wave-uniform: does the last query of the block see the first key of the wavefront?
-      const bool any_visible = !s.causal || (s.q_offset + blk_i0 + 31 >= k0 + wave_key0);
-      if (blk_i0 < s.Sq && any_visible) {
+      {  // every block of the walk is computed; (row, key) pairs that are not visible are masked
         f32x16 sc[NB], dp[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)

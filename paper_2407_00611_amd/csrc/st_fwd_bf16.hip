@@ -677,7 +677,7 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
   }();
   static const int pipe = [] {
     const char* e = getenv("ST_FWD_PIPE");
-    return e ? atoi(e) : 1;
+    return e ? atoi(e) : 0;
   }();
   if (pipe) return launch_fwd_pipe(a, stream);
   return wq == 64 ? launch_fwd_bf16_wq<64>(a, stream) : launch_fwd_bf16_wq<32>(a, stream);
