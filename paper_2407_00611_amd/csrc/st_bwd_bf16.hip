@@ -31,7 +31,7 @@ __device__ __forceinline__ int visible_keys(int causal, int Sk, int64_t qpos, in
 // dQ kernel
 // =============================================================================================
 #ifndef ST_DQ_WQ
-#define ST_DQ_WQ 64
+#define ST_DQ_WQ 32
 #endif
 #ifndef ST_DKV_WK
 #define ST_DKV_WK 32
@@ -44,7 +44,7 @@ template <int D>
 __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(const BwdArgs a) {
   constexpr int QB = kQ_WQ / 32, KB = kQ_BN / 32, KS = D / 16, DB = D / 32;
   constexpr int kTile = kQ_BN * D * 2;           // bytes of one K (or V) tile
-  __shared__ __attribute__((aligned(16))) char smem_raw[4 * kTile];   // 2 stages x (K, V)
+  __shared__ __attribute__((aligned(1024))) char smem_raw[4 * kTile];   // 2 stages x (K, V)
   ST_LDS char* smem = (ST_LDS char*)smem_raw;
 
   const Shape& s = a.s;
@@ -102,19 +102,14 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
   int c_cur = 0, t_cur = 0, n_cur = 0;
   while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) == 0) ++c_cur;
 
-  StageRegs<D, kQ_BN> rk, rv;
-  auto issue_load = [&](int c, int t) {
+  auto issue_load = [&](int c, int t, int stage) {
     const char* kb = (const char*)a.t.k[c] + ((int64_t)b * a.t.ksb + (int64_t)hk * a.t.ksh) * 2;
     const char* vb = (const char*)a.t.v[c] + ((int64_t)b * a.t.vsb + (int64_t)hk * a.t.vsh) * 2;
-    stage_load<D, kQ_BN>(rk, kb, a.t.kss, t * kQ_BN, s.Sk, tid);
-    stage_load<D, kQ_BN>(rv, vb, a.t.vss, t * kQ_BN, s.Sk, tid);
+    stage_dma<D, kQ_BN>(kb, a.t.kss, t * kQ_BN, s.Sk, smem + stage * 2 * kTile, tid);
+    stage_dma<D, kQ_BN>(vb, a.t.vss, t * kQ_BN, s.Sk, smem + stage * 2 * kTile + kTile, tid);
   };
   int buf = 0;
-  if (c_cur < a.t.n) {
-    issue_load(c_cur, 0);
-    stage_store<D, kQ_BN>(rk, smem, tid);
-    stage_store<D, kQ_BN>(rv, smem + kTile, tid);
-  }
+  if (c_cur < a.t.n) issue_load(c_cur, 0, 0);
   __syncthreads();
 
   while (c_cur < a.t.n) {
@@ -125,18 +120,17 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
       while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) == 0) ++c_nxt;
     }
     const bool have_next = c_nxt < a.t.n;
-    if (have_next) issue_load(c_nxt, t_nxt);
+    if (have_next) issue_load(c_nxt, t_nxt, buf ^ 1);
 
     const int64_t k0 = a.t.k_offset[c_cur];
     const int tile_k0 = t_cur * kQ_BN;
     const int nv_wave_min = visible_keys(s.causal, s.Sk, s.q_offset + wave_first_row, k0);
-    const int nv_wave_max = wave_live ? visible_keys(s.causal, s.Sk, s.q_offset + wave_last_row, k0) : 0;
     const ST_LDS char* ktile = smem + buf * 2 * kTile;
     const ST_LDS char* vtile = ktile + kTile;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) {
       const int blk_k0 = tile_k0 + 32 * kb;
-      if (blk_k0 < nv_wave_max) {                              // wave-uniform
+      {  // every wavefront computes every block the workgroup walks; invisible pairs are masked
         f32x16 sc[QB], dp[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
@@ -184,10 +178,6 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
       }
     }
 
-    if (have_next) {
-      stage_store<D, kQ_BN>(rk, smem + (buf ^ 1) * 2 * kTile, tid);
-      stage_store<D, kQ_BN>(rv, smem + (buf ^ 1) * 2 * kTile + kTile, tid);
-    }
     __syncthreads();
     buf ^= 1;
     c_cur = c_nxt;

@@ -479,14 +479,18 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
       // The empty asm statements pin this otherwise pure arithmetic between the scheduling fences of
       // its slot: instruction selection orders side-effect-free code freely, and the fences only bind
       // the later machine scheduler.
-      auto exp_issue = [&](int e0, int e1) {     // at most four elements per slot
-        float x[4] = {0.f, 0.f, 0.f, 0.f};
+      auto exp_issue = [&](int e0, int e1) {     // at most three elements per slot
+        float x[3] = {0.f, 0.f, 0.f};
 #pragma unroll
         for (int e = e0; e < e1; ++e) x[e - e0] = sc[(e / 8) % 2][8 * (e / 16) + e % 8];
-        asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
+        if (e1 - e0 == 3) asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]));
+        else if (e1 - e0 == 2) asm volatile("" : "+v"(x[0]), "+v"(x[1]));
+        else if (e1 - e0 == 1) asm volatile("" : "+v"(x[0]));
 #pragma unroll
         for (int e = e0; e < e1; ++e) x[e - e0] = __builtin_amdgcn_exp2f(fmaf(x[e - e0], c_exp, -mc[(e / 8) % 2]));
-        asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]));
+        if (e1 - e0 == 3) asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]));
+        else if (e1 - e0 == 2) asm volatile("" : "+v"(x[0]), "+v"(x[1]));
+        else if (e1 - e0 == 1) asm volatile("" : "+v"(x[0]));
 #pragma unroll
         for (int e = e0; e < e1; ++e) pv[e] = x[e - e0];
       };
@@ -677,7 +681,7 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
   }();
   static const int pipe = [] {
     const char* e = getenv("ST_FWD_PIPE");
-    return e ? atoi(e) : 0;
+    return e ? atoi(e) : 1;
   }();
   if (pipe) return launch_fwd_pipe(a, stream);
   return wq == 64 ? launch_fwd_bf16_wq<64>(a, stream) : launch_fwd_bf16_wq<32>(a, stream);
