@@ -13,6 +13,8 @@
 //
 // Both recompute S and dP (seven contractions instead of five) so that every accumulator has a
 // single owner: dQ is written once per launch, dK/dV once per workgroup, bit-reproducibly.
+#include <cstdlib>
+
 #include "st_internal.h"
 #include "st_mfma.h"
 
@@ -252,6 +254,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   const int q_tile_first = wg_i0 / kK_BQ;
   const int n_q_tiles = (s.Sq + kK_BQ - 1) / kK_BQ;
   if (q_tile_first >= n_q_tiles) return;
+  // Query blocks of this workgroup: [q_tile_first, q_split) and [q_resume, n_q_tiles).  The gap, if any,
+  // belongs to the fast kernel (full blocks that see every key of the enclosing full 256-key tile).
+  int q_split = n_q_tiles, q_resume = n_q_tiles;
+  if (a.dkv_fast && kK_BQ == kDkvFastRows) {
+    const int tile_key0 = wg_key0 / kDkvFastKeys * kDkvFastKeys;
+    if (tile_key0 + kDkvFastKeys <= s.Sk) {
+      const int fb = dkv_fast_first_block(s.causal, s.q_offset, k0, tile_key0), n_full = s.Sq / kDkvFastRows;
+      if (fb < n_full) {
+        q_split = fb > q_tile_first ? fb : q_tile_first;
+        q_resume = n_full;
+      }
+    }
+  }
 
   // resident K, V fragments (B operands, column = key)
   const char* kbase = (const char*)a.t.k[c] + ((int64_t)b * a.t.ksb + (int64_t)hk * a.t.ksh) * 2;
@@ -281,13 +296,19 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   const float c_exp = s.scale * kLog2e;
 
   // flattened (head of the group, query tile) walk
-  const int tiles_per_head = n_q_tiles - q_tile_first;
+  const int n_head_lo = q_split - q_tile_first;
+  const int tiles_per_head = n_head_lo + (n_q_tiles - q_resume);
+  if (tiles_per_head <= 0) return;
   const int n_steps = G * tiles_per_head;
+  auto tile_of = [&](int step) -> int {
+    const int j = step % tiles_per_head;
+    return j < n_head_lo ? q_tile_first + j : q_resume + (j - n_head_lo);
+  };
   StageRegs<D, kK_BQ> rq, rdo;
   float stat_reg = 0.f;   // threads 0..63: lse2 of row tid; threads 64..127: delta of row tid-64
   auto issue_load = [&](int step) {
     const int h = hk * G + step / tiles_per_head;
-    const int i0 = (q_tile_first + step % tiles_per_head) * kK_BQ;
+    const int i0 = tile_of(step) * kK_BQ;
     const char* qb_ = (const char*)a.q.ptr + ((int64_t)b * a.q.sb + (int64_t)h * a.q.sh) * 2;
     const char* dob_ = (const char*)a.d_o.ptr + ((int64_t)b * a.d_o.sb + (int64_t)h * a.d_o.sh) * 2;
     stage_load<D, kK_BQ>(rq, qb_, a.q.ss, i0, s.Sq, tid);
@@ -322,7 +343,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
     const bool have_next = step + 1 < n_steps;
     if (have_next) issue_load(step + 1);
 
-    const int i0 = (q_tile_first + step % tiles_per_head) * kK_BQ;
+    const int i0 = tile_of(step) * kK_BQ;
     const ST_LDS char* qtile = smem + buf * kStage;
     const ST_LDS char* dotile = qtile + kTile;
     const ST_LDS float* lse_s = reinterpret_cast<const ST_LDS float*>(qtile + 2 * kTile);
@@ -431,7 +452,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
 
 }  // namespace
 
-hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t stream) {
+hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
+  BwdArgs a = a_in;
   if (a.t.n <= 0 || a.s.Sq <= 0 || a.s.Sk <= 0) return hipSuccess;
   const int n_qt = (a.s.Sq + kQ_BM - 1) / kQ_BM;
   const int64_t total_q = (int64_t)n_qt * a.s.Hq * a.s.B;
@@ -439,13 +461,23 @@ hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t stream) {
   const int64_t total_k = (int64_t)n_kt * a.s.Hkv * a.s.B * a.t.n;
   if (total_q > 0x7fffffff || total_k > 0x7fffffff) return hipErrorInvalidValue;
   if (a.s.D != 128 && a.s.D != 64) return hipErrorInvalidValue;
+  // tuning / debugging override: ST_DKV_FAST=0 keeps all dK/dV work in the general kernel
+  static const int fast_env = [] {
+    const char* e = getenv("ST_DKV_FAST");
+    return e ? atoi(e) : 1;
+  }();
+  a.dkv_fast = (fast_env && dkv_fast_usable(a)) ? 1 : 0;
   {
-    ProfScope prof("bwd_dkv_bf16", stream);
+    ProfScope prof(a.dkv_fast ? "bwd_dkv_edge" : "bwd_dkv_bf16", stream);
     if (a.s.D == 128) hipLaunchKernelGGL(bwd_dkv_bf16_kernel<128>, dim3((unsigned)total_k), dim3(256), 0, stream, a);
     else hipLaunchKernelGGL(bwd_dkv_bf16_kernel<64>, dim3((unsigned)total_k), dim3(256), 0, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (a.dkv_fast) {
+    e = launch_bwd_dkv_fast(a, stream);
+    if (e != hipSuccess) return e;
+  }
   {
     ProfScope prof("bwd_dq_bf16", stream);
     if (a.s.D == 128) hipLaunchKernelGGL(bwd_dq_bf16_kernel<128>, dim3((unsigned)total_q), dim3(256), 0, stream, a);

@@ -50,7 +50,21 @@ struct BwdArgs {
   float* dq;           // fp32 [B,Sq,Hq,D], +=
   float* dk[kMaxTable];  // fp32 [B,Sk,Hkv,D] per table entry, +=
   float* dv[kMaxTable];
+  int32_t dkv_fast;    // 1: the fast dK/dV kernel runs too and owns the blocks dkv_fast_first_block describes
 };
+
+// Split of the dK/dV work between the general kernel and the fast one (head_dim 128): the fast kernel
+// takes, for every FULL tile of kDkvFastKeys keys, the full kDkvFastRows-query blocks from the first one
+// whose rows all see the tile's last key; everything else (masked blocks, ragged tails) stays general.
+constexpr int kDkvFastKeys = 256;
+constexpr int kDkvFastRows = 32;
+__host__ __device__ inline int dkv_fast_first_block(int causal, int64_t q_offset, int64_t k0, int tile_key0) {
+  if (!causal) return 0;
+  const int64_t d = k0 + tile_key0 + kDkvFastKeys - 1 - q_offset;   // first row index that sees the last key
+  if (d <= 0) return 0;
+  const int64_t fb = (d + kDkvFastRows - 1) / kDkvFastRows;
+  return fb > 0x3fffffff ? 0x3fffffff : (int)fb;
+}
 
 // Optional per-kernel timing (st_profile_begin / st_profile_end): while enabled, a ProfScope
 // records a HIP event on the launch stream before and after the kernel it brackets.
@@ -66,6 +80,8 @@ hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
+bool dkv_fast_usable(const BwdArgs& a);
+hipError_t launch_bwd_dkv_fast(const BwdArgs& a, hipStream_t s);
 
 hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, void* o_lowp, int lowp_dtype,

@@ -20,6 +20,11 @@ STEP_CASES = [
     ("noncausal_d64", 1, 4, 4, 64, 515, 64, 3, 0, False),
     ("one_row_one_key", 1, 1, 1, 128, 1, 1, 1, 0, True),
     ("wide_kv_tile", 1, 2, 1, 128, 130, 600, 1, 450, True),
+    # head_dim 128 with full 256-key tiles: the hand-scheduled dK/dV loop takes the fully visible 32-row blocks
+    ("fast_one_block", 1, 2, 2, 128, 32, 256, 1, 0, False),
+    ("fast_gqa_two_tiles", 2, 4, 2, 128, 160, 512, 2, 700, True),
+    ("fast_three_heads_ragged", 1, 3, 1, 128, 103, 296, 2, 1000, True),
+    ("fast_long_run", 1, 2, 1, 128, 416, 256, 2, 256, True),
 ]
 
 
