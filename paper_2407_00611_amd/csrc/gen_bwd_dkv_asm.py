@@ -24,6 +24,8 @@ by every wavefront (identical values), so that no per-element VALU work is spent
 """
 import sys
 
+from st_asmgen import Emitter, ar, sr, vr, write_inc
+
 # ------------------------------------------------------------------------------------------------
 # register map
 # ------------------------------------------------------------------------------------------------
@@ -74,64 +76,6 @@ LDS_BYTES = VT + 65536
 
 LAT = 3          # MFMA slots between the issue of an LDS read and its first use
 BUDGET = 6       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
-
-
-def vr(a, n=1):
-    return f"v{a}" if n == 1 else f"v[{a}:{a + n - 1}]"
-
-def ar(a, n=1):
-    return f"a{a}" if n == 1 else f"a[{a}:{a + n - 1}]"
-
-def sr(a, n=1):
-    return f"s{a}" if n == 1 else f"s[{a}:{a + n - 1}]"
-
-
-class Emitter:
-    def __init__(self):
-        self.lines = []
-        self.n_instr = 0
-        self.label_id = 0
-        # LDS reads in flight, oldest first: list of tags
-        self.ds = []
-        self.last_valu_write = {}   # register -> instruction index of the VALU that wrote it
-
-    def raw(self, s):
-        self.lines.append(s)
-        if not s.endswith(":") and not s.startswith(";"):
-            self.n_instr += 1
-
-    def comment(self, s):
-        self.lines.append("; " + s)
-
-    def label(self, base):
-        self.label_id += 1
-        return f".L{base}_{self.label_id}_%="
-
-    # ---- LDS read tracking (reads return in order, lgkmcnt counts the ones still in flight)
-    def ds_read(self, text, tag):
-        assert len(self.ds) < 15, "too many LDS reads in flight for the 4-bit counter"
-        self.raw(text)
-        self.ds.append(tag)
-
-    def need(self, tag):
-        if tag in self.ds:
-            i = self.ds.index(tag)
-            n = len(self.ds) - i - 1
-            self.raw(f"s_waitcnt lgkmcnt({n})")
-            self.ds = self.ds[i + 1:]
-
-    def valu(self, text, writes=()):
-        self.raw(text)
-        for r in writes:
-            self.last_valu_write[r] = self.n_instr
-
-    def mfma(self, dst, a, b, c, breads=()):
-        # a VALU result must be two instructions old before an MFMA reads it
-        for r in breads:
-            w = self.last_valu_write.get(r)
-            if w is not None and self.n_instr - w < 2:
-                self.raw("s_nop 1")
-        self.raw(f"v_mfma_f32_32x32x16_bf16 {dst}, {a}, {b}, {c}")
 
 
 def gen_step(e: Emitter, u: int):
@@ -494,19 +438,9 @@ def generate():
 
 def main():
     e = generate()
-    out = ["// generated by gen_bwd_dkv_asm.py - do not edit", f"#define ST_DKV_FAST_LDS_BYTES {LDS_BYTES}"]
-    out.append(f"#define ST_DKV_FAST_NINSTR {e.n_instr}")
-    clob = [f'"v{i}"' for i in range(256) if not (IN_V <= i < IN_V + 16)] + [f'"a{i}"' for i in range(256)]
-    clob += [f'"s{S_CEXP}"'] + [f'"s{i}"' for i in range(64, 92)] + ['"vcc"', '"memory"']
-    out.append("#define ST_DKV_FAST_CLOBBERS " + ", ".join(clob))
-    out.append("#define ST_DKV_FAST_ASM \\")
-    for ln in e.lines:
-        if ln.startswith(";"):
-            out.append(f"  /* {ln[2:]} */ \\")
-        else:
-            out.append('  "' + ln + '\\n\\t" \\')
-    out.append('  ""')
-    sys.stdout.write("\n".join(out) + "\n")
+    clob = [f"v{i}" for i in range(256) if not (IN_V <= i < IN_V + 16)] + [f"a{i}" for i in range(256)]
+    clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 92)]
+    write_inc(sys.stdout, "gen_bwd_dkv_asm.py", "ST_DKV_FAST", e, LDS_BYTES, clob)
 
 
 if __name__ == "__main__":

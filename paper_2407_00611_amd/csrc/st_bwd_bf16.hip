@@ -101,8 +101,14 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
     const int nv = visible_keys(s.causal, s.Sk, s.q_offset + wg_last_row, a.t.k_offset[c]);
     return (nv + kQ_BN - 1) / kQ_BN;
   };
+  // first tile of a chunk that is this kernel's: the leading ones may belong to the fast kernel
+  const int fast_row0 = qt * kQ_BM / kDqFastRows * kDqFastRows;
+  const bool fast_on = a.dq_fast && kQ_BN == kDqFastKeys && fast_row0 + kDqFastRows <= s.Sq;
+  auto chunk_t0 = [&](int c) -> int {
+    return fast_on ? dq_fast_tiles(s.causal, s.Sk, s.q_offset, fast_row0, a.t.k_offset[c]) : 0;
+  };
   int c_cur = 0, t_cur = 0, n_cur = 0;
-  while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) == 0) ++c_cur;
+  while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) <= (t_cur = chunk_t0(c_cur))) ++c_cur;
 
   auto issue_load = [&](int c, int t, int stage) {
     const char* kb = (const char*)a.t.k[c] + ((int64_t)b * a.t.ksb + (int64_t)hk * a.t.ksh) * 2;
@@ -111,15 +117,14 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
     stage_dma<D, kQ_BN>(vb, a.t.vss, t * kQ_BN, s.Sk, smem + stage * 2 * kTile + kTile, tid);
   };
   int buf = 0;
-  if (c_cur < a.t.n) issue_load(c_cur, 0, 0);
+  if (c_cur < a.t.n) issue_load(c_cur, t_cur, 0);
   __syncthreads();
 
   while (c_cur < a.t.n) {
     int c_nxt = c_cur, t_nxt = t_cur + 1, n_nxt = n_cur;
     if (t_nxt >= n_cur) {
-      t_nxt = 0;
       ++c_nxt;
-      while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) == 0) ++c_nxt;
+      while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) <= (t_nxt = chunk_t0(c_nxt))) ++c_nxt;
     }
     const bool have_next = c_nxt < a.t.n;
     if (have_next) issue_load(c_nxt, t_nxt, buf ^ 1);
@@ -478,12 +483,20 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
     e = launch_bwd_dkv_fast(a, stream);
     if (e != hipSuccess) return e;
   }
+  static const int dq_fast_env = [] {
+    const char* e = getenv("ST_DQ_FAST");
+    return e ? atoi(e) : 1;
+  }();
+  a.dq_fast = (dq_fast_env && dq_fast_usable(a)) ? 1 : 0;
   {
-    ProfScope prof("bwd_dq_bf16", stream);
+    ProfScope prof(a.dq_fast ? "bwd_dq_edge" : "bwd_dq_bf16", stream);
     if (a.s.D == 128) hipLaunchKernelGGL(bwd_dq_bf16_kernel<128>, dim3((unsigned)total_q), dim3(256), 0, stream, a);
     else hipLaunchKernelGGL(bwd_dq_bf16_kernel<64>, dim3((unsigned)total_q), dim3(256), 0, stream, a);
   }
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.dq_fast) return launch_bwd_dq_fast(a, stream);
+  return hipSuccess;
 }
 
 }  // namespace st

@@ -51,6 +51,7 @@ struct BwdArgs {
   float* dk[kMaxTable];  // fp32 [B,Sk,Hkv,D] per table entry, +=
   float* dv[kMaxTable];
   int32_t dkv_fast;    // 1: the fast dK/dV kernel runs too and owns the blocks dkv_fast_first_block describes
+  int32_t dq_fast;     // 1: the fast dQ kernel runs too and owns the tiles dq_fast_tiles describes
 };
 
 // Split of the dK/dV work between the general kernel and the fast one (head_dim 128): the fast kernel
@@ -75,6 +76,19 @@ struct ProfScope {
   hipStream_t stream;
 };
 
+// Split of the dQ work (head_dim 128): for every FULL tile of kDqFastRows queries the fast kernel takes,
+// of each chunk, the leading kDqFastKeys-key tiles that the tile's first row (hence every row) sees in full.
+constexpr int kDqFastRows = 256;
+constexpr int kDqFastKeys = 64;
+__host__ __device__ inline int dq_fast_tiles(int causal, int Sk, int64_t q_offset, int row0, int64_t k0) {
+  int64_t nv = Sk;
+  if (causal) {
+    nv = q_offset + row0 - k0 + 1;
+    nv = nv < 0 ? 0 : (nv > Sk ? Sk : nv);
+  }
+  return (int)(nv / kDqFastKeys);
+}
+
 // ---- launchers (each returns hipGetLastError() after the launch) ----
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
@@ -82,6 +96,8 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
 bool dkv_fast_usable(const BwdArgs& a);
 hipError_t launch_bwd_dkv_fast(const BwdArgs& a, hipStream_t s);
+bool dq_fast_usable(const BwdArgs& a);
+hipError_t launch_bwd_dq_fast(const BwdArgs& a, hipStream_t s);
 
 hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, void* o_lowp, int lowp_dtype,

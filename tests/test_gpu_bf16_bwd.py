@@ -25,6 +25,11 @@ STEP_CASES = [
     ("fast_gqa_two_tiles", 2, 4, 2, 128, 160, 512, 2, 700, True),
     ("fast_three_heads_ragged", 1, 3, 1, 128, 103, 296, 2, 1000, True),
     ("fast_long_run", 1, 2, 1, 128, 416, 256, 2, 256, True),
+    # full 256-query tiles: the hand-scheduled dQ loop takes the fully visible 64-key tiles of every chunk
+    ("dq_fast_one_tile", 1, 1, 1, 128, 256, 64, 1, 0, False),
+    ("dq_fast_two_tiles", 1, 1, 1, 128, 256, 128, 1, 0, False),
+    ("dq_fast_chunk_switches", 2, 4, 2, 128, 300, 320, 3, 0, False),
+    ("dq_fast_causal_mix", 1, 2, 1, 128, 512, 200, 5, 520, True),
 ]
 
 
