@@ -1,0 +1,486 @@
+#!/usr/bin/env python3
+"""Generates the gfx950 assembly of the forward main loop (head_dim 128) as a C string literal.
+
+    python gen_fwd_asm.py > st_fwd_asm.inc      (build.py does this before compiling)
+
+Body of ONE `asm volatile` statement in st_fwd_fast.hip.  A workgroup (4 wavefronts) owns 256 queries of
+one head, 64 per wavefront as two 32-query blocks, and walks the 64-key tiles that every one of its rows
+sees in full; it writes the partial (O, lse) of those tiles.  Everything else (masked tiles, ragged tails,
+ragged query tiles) is done afterwards by the general kernel, which folds its own partial state into this
+one with the log-sum-exp merge.
+
+MFMA C layout "lane = query column": the exponent reference r (log2 units) and the row sum are one
+register per lane and query block.  The reference is lazy: it only moves, by a whole number of log2 units,
+when a block's maximum exceeds it by more than GAP, so the rescale factor is an exact power of two and the
+common path never touches the accumulators.
+
+Per 32-key block i and wavefront two groups of 16 MFMAs, software-pipelined two blocks deep:
+    group B   O^T += V^T P^T(i)          A: V^T of block i by LDS transpose reads, B: packed P(i)
+    group A   S^T(i+2) = K Q^T           A: K rows of block i+2 from LDS,          B: Q fragments (AGPRs)
+    VALU      slots 3..9: row maximum of S(i+1), both halves, and the test against the reference
+              (rare: call the rescale routine);  slots 10..31: P(i+1) = exp2(S c - r), bf16 pack, row sums
+K / V tiles (64 keys) arrive by direct global->LDS loads into a 4-stage ring, three tiles ahead; one
+barrier per tile.  The chunk table (base pointers, tiles per chunk) sits in LDS, written by the C++ side.
+"""
+import sys
+
+from st_asmgen import Emitter, ar, sr, vr, write_inc
+
+KS, DB, QB, NS = 8, 4, 2, 4
+GAP = 8.0                                            # log2 units a block maximum may exceed the reference by
+
+# ---- AGPRs
+def ACC(db, qb): return 16 * (2 * db + qb)
+def QF(qb, ks): return 128 + 4 * (8 * qb + ks)
+
+# ---- VGPRs
+def SBUF(buf, qb): return 32 * buf + 16 * qb        # two score buffers (S, then P in fp32)
+def P16(buf, qb, m): return 64 + 16 * buf + 8 * qb + 4 * m
+def NL(qb): return 96 + qb                          # -r: minus the exponent reference, log2 units
+def LSUM(qb, m): return 98 + 2 * qb + m             # partial row sums (this lane's key rows)
+def MX(qb): return 102 + qb                         # block maximum, then d = max * c - r
+ONES, GAPR, DMAX = 104, 105, 106                     # packed bf16 (1, 1); GAP; max over both query blocks of d
+TMP = 108                                            # 108..119
+POOL0 = 120                                          # 2 rings x 4 fragments x 4 registers
+XL, XH = 152, 160
+TRLO_L, TRHI_L, TRLO_H, TRHI_H = 168, 172, 176, 180
+KOFF, VOFF = 184, 188
+OOFF, LSEOFF = 192, 193
+RT = 200                                             # 200..223: temporaries of the rescale routine
+# inputs (pinned by the C++ side): v[224:239]
+I_QROW0, I_QROW1, I_XBASE, I_GF16, I_TRBASE, I_LF16, I_KOFF0, I_VOFF0, I_OOFF, I_LSEOFF = (
+    224, 226, 228, 229, 230, 231, 232, 233, 234, 235)
+(S_LDS, S_WAVE, S_NT, S_KRS16, S_VRS16, S_SCALE, S_OPTR, S_OQB, S_TBL, S_KTILE, S_VTILE, S_LSEPTR) = (
+    32, 33, 34, 35, 36, 37, 38, 40, 41, 42, 43, 44)
+# scalar temporaries
+S_CEXP, T_M0, T_REM, D_KPTR, D_VPTR, D_LEFT, D_IDX, D_TBL, T_X = 47, 64, 65, 66, 68, 70, 71, 72, 73
+T_RET, T_RARE = 76, 78                               # return address; address of rescale routine b at 78 + 2 b
+
+# ---- LDS map
+def KT(s): return 32768 * s
+def VT(s): return 32768 * s + 16384
+TBL = 32768 * NS
+LDS_BYTES = TBL + 2048
+
+LAT = 3
+BUDGET = 7
+BRANCH_SLOT = 9                                      # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
+
+
+class Pipe:
+    def __init__(self, e):
+        self.e = e
+        self.frag_reg, self.uses_left, self.owner = {}, {}, {}
+
+    def alloc(self, ring, idx, tag, uses):
+        slot = 4 * ring + idx % 4
+        old = self.owner.get(slot)
+        assert old is None or self.uses_left[old] == 0, f"fragment {old} overwritten by {tag} before its last use"
+        self.owner[slot] = tag
+        self.uses_left[tag] = uses
+        self.frag_reg[tag] = POOL0 + 4 * slot
+        return POOL0 + 4 * slot
+
+    def use(self, tag):
+        assert self.uses_left[tag] > 0, tag
+        self.uses_left[tag] -= 1
+        return self.frag_reg[tag]
+
+    def snapshot(self):
+        return list(self.e.ds), dict(self.frag_reg), dict(self.uses_left), dict(self.owner)
+
+    def restore(self, snap):
+        self.e.ds, self.frag_reg, self.uses_left, self.owner = list(snap[0]), dict(snap[1]), dict(snap[2]), dict(snap[3])
+
+
+def xreg(stage, ks): return (XL if stage < 2 else XH) + ks
+def trregs(stage): return (TRLO_L, TRHI_L) if stage < 2 else (TRLO_H, TRHI_H)
+def imm(stage, base): return base - (0 if stage < 2 else 65536)
+
+
+def read_k(p, blk, ks, seq):
+    stage, kb = blk
+    tag = f"k{seq}_{ks}"
+    r = p.alloc(0, ks, tag, QB)
+    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, KT(stage)) + 8192 * kb}", tag)
+
+
+def read_vt(p, blk, m, db, seq):
+    """V^T fragment (32 d rows x 16 keys) of a block: A operand of O^T += V^T P^T."""
+    stage, kb = blk
+    tag = f"t{seq}_{m}_{db}"
+    r = p.alloc(1, 4 * m + db, tag, QB)
+    lo, hi = trregs(stage)
+    off = imm(stage, VT(stage)) + 8192 * kb + 4096 * m
+    p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r, 2)}, {vr(lo + db)} offset:{off}", tag + "lo")
+    p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(hi + db)} offset:{off}", tag)
+
+
+def valu_max(buf):
+    """Row maximum of S in buffer `buf`, both halves of the wavefront, and d = max * c - r per query block."""
+    out = []
+    for qb in range(QB):
+        s0 = SBUF(buf, qb)
+        out.append(f"v_max3_f32 {vr(MX(qb))}, {vr(s0)}, {vr(s0 + 1)}, {vr(s0 + 2)}")
+        for v in range(3, 15, 2):
+            out.append(f"v_max3_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(s0 + v)}, {vr(s0 + v + 1)}")
+        out.append(f"v_max_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(s0 + 15)}")
+    # the two halves hold different key rows of the same query column: exchange and combine
+    for qb in range(QB):
+        out.append(f"v_mov_b32 {vr(TMP + qb)}, {vr(MX(qb))}")
+    out.append("s_nop 1")
+    for qb in range(QB):
+        out.append(f"v_permlane32_swap_b32 {vr(TMP + qb)}, {vr(MX(qb))}")
+    out.append("s_nop 1")
+    for qb in range(QB):
+        out.append(f"v_max_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(TMP + qb)}")
+    for qb in range(QB):
+        out.append(f"v_fma_f32 {vr(MX(qb))}, {vr(MX(qb))}, {sr(S_CEXP)}, {vr(NL(qb))}")
+    out.append(f"v_max_f32 {vr(DMAX)}, {vr(MX(0))}, {vr(MX(1))}")
+    return out
+
+
+def valu_exp(sbuf, pbuf):
+    """P = exp2(S c - r) in place, packed to bf16 into P buffer `pbuf`, row sums of the packed values."""
+    out = []
+    for qb in range(QB):
+        for m in range(2):
+            rs = [SBUF(sbuf, qb) + 8 * m + i for i in range(8)]
+            for half in range(2):
+                for r in rs[4 * half:4 * half + 4]:
+                    out.append((f"v_fma_f32 {vr(r)}, {vr(r)}, {sr(S_CEXP)}, {vr(NL(qb))}", (), 1))
+                for r in rs[4 * half:4 * half + 4]:
+                    out.append((f"v_exp_f32 {vr(r)}, {vr(r)}", (), 2))
+            for i in range(4):
+                d = P16(pbuf, qb, m) + i
+                out.append((f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(rs[2 * i])}, {vr(rs[2 * i + 1])}", (d,), 1))
+            for i in range(4):
+                out.append((f"v_dot2c_f32_bf16 {vr(LSUM(qb, m))}, {vr(P16(pbuf, qb, m) + i)}, {vr(ONES)}", (), 1))
+    return out
+
+
+def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, prefetch=True):
+    """Block i = cur, i+1 = nxt (its V^T is prefetched at the tail), i+2 = nxt2 (its K feeds group A).
+    par = i % 2: P(i) sits in P buffer par, S(i+1) in score buffer 1 - par, S(i+2) goes to score buffer par."""
+    e = p.e
+    e.comment(f"======== block {cur}: O^T += V^T P^T{cur} | S^T{nxt2} -> buffer {par} | softmax of {nxt}")
+    reads = {k: [] for k in range(-1, 32)}
+
+    def plan(first_use, fn):
+        reads[max(first_use - LAT, -1)].append(fn)
+
+    slots = []
+    for m in range(2):
+        for db in range(DB):
+            k = 2 * (4 * m + db)
+            if not (m == 0 and db < 2):                   # requested at the tail of the block before
+                plan(k, (lambda m=m, db=db: read_vt(p, cur, m, db, seq)))
+            for qb in range(QB):
+                slots.append(("B", m, db, qb))
+    if do_a:
+        for ks in range(KS):
+            plan(16 + 2 * ks, (lambda ks=ks: read_k(p, nxt2, ks, seq)))
+            for qb in range(QB):
+                slots.append(("A", ks, qb))
+    else:
+        slots += [None] * 16
+    if prefetch and nxt is not None:
+        for db in range(2):
+            reads[29 + db].append(lambda db=db: read_vt(p, nxt, 0, db, seq + 1))
+
+    valu_m = valu_max(1 - par) if do_valu else []
+    valu_e = valu_exp(1 - par, 1 - par) if do_valu else []
+    mi, vi = [0], [0]
+
+    if head is not None:
+        head()
+    for fn in reads[-1]:
+        fn()
+    for k, sl in enumerate(slots):
+        if sl is not None and sl[0] == "B":
+            _, m, db, qb = sl
+            tag = f"t{seq}_{m}_{db}"
+            e.need(tag)
+            acc = ar(ACC(db, qb), 16)
+            e.mfma(acc, vr(p.use(tag), 4), vr(P16(par, qb, m), 4), acc)
+        elif sl is not None:
+            _, ks, qb = sl
+            tag = f"k{seq}_{ks}"
+            e.need(tag)
+            d = vr(SBUF(par, qb), 16)
+            e.mfma(d, vr(p.use(tag), 4), ar(QF(qb, ks), 4), "0" if ks == 0 else d)
+        units = 0
+        for fn in reads[k]:
+            n0 = len(e.ds)
+            fn()
+            units += len(e.ds) - n0
+        if do_valu:
+            # S(i+1) was written by the last group of the block before: first reader three MFMA issues later
+            while 3 <= k <= BRANCH_SLOT and mi[0] < len(valu_m) and (units < BUDGET or k == BRANCH_SLOT):
+                e.raw(valu_m[mi[0]])
+                mi[0] += 1
+                units += 1
+            if k == BRANCH_SLOT:
+                l_cont = e.label("cont")
+                e.raw(f"v_cmp_gt_f32 vcc, {vr(DMAX)}, {vr(GAPR)}")
+                e.raw("s_cmp_lg_u64 vcc, 0")
+                e.raw(f"s_cbranch_scc0 {l_cont}")
+                e.raw(f"s_swappc_b64 {sr(T_RET, 2)}, {sr(T_RARE + 2 * par, 2)}")
+                e.raw(l_cont + ":")
+            while k > BRANCH_SLOT and vi[0] < len(valu_e) and units + valu_e[vi[0]][2] <= BUDGET:
+                e.valu(valu_e[vi[0]][0], valu_e[vi[0]][1])
+                units += valu_e[vi[0]][2]
+                vi[0] += 1
+    leftover = len(valu_e) - vi[0]
+    while vi[0] < len(valu_e):           # what did not fit under the MFMAs (the pipeline stalls on it)
+        e.valu(valu_e[vi[0]][0], valu_e[vi[0]][1])
+        vi[0] += 1
+    return leftover if do_a else 0
+
+
+def gen_rescale_routine(e, pbuf):
+    """Called when some row's block maximum exceeds its reference by more than GAP.  MFMA slots 0..BRANCH_SLOT of
+    the calling block have been issued (all of m = 0 and db = 0 of m = 1); the rest of m = 1 still reads P buffer
+    `pbuf`.  Moves the reference of the jumping rows up by k = ceil(d) log2 units: accumulators, row sums and
+    the pending packed P values are multiplied by 2^-k (exact)."""
+    e.raw("s_nop 7")
+    e.raw("s_nop 7")
+    e.raw("s_nop 7")
+    alpha = [RT, RT + 1]
+    for qb in range(QB):
+        k, ki = RT + 2 + qb, RT + 4 + qb
+        e.raw(f"v_ceil_f32 {vr(k)}, {vr(MX(qb))}")
+        e.raw(f"v_cmp_gt_f32 vcc, {vr(MX(qb))}, {vr(GAPR)}")
+        e.raw("s_nop 1")
+        e.raw(f"v_cndmask_b32 {vr(k)}, 0, {vr(k)}, vcc")
+        e.raw(f"v_sub_f32 {vr(NL(qb))}, {vr(NL(qb))}, {vr(k)}")
+        e.raw(f"v_cvt_i32_f32 {vr(ki)}, {vr(k)}")
+        e.raw(f"v_sub_u32 {vr(ki)}, 0, {vr(ki)}")
+        e.raw(f"v_ldexp_f32 {vr(alpha[qb])}, 1.0, {vr(ki)}")
+        for m in range(2):
+            e.raw(f"v_mul_f32 {vr(LSUM(qb, m))}, {vr(alpha[qb])}, {vr(LSUM(qb, m))}")
+    t = RT + 8
+    for qb in range(QB):
+        for db in range(DB):
+            for v0 in range(0, 16, 8):
+                for i in range(8):
+                    e.raw(f"v_accvgpr_read_b32 {vr(t + i)}, {ar(ACC(db, qb) + v0 + i)}")
+                for i in range(8):
+                    e.raw(f"v_mul_f32 {vr(t + i)}, {vr(alpha[qb])}, {vr(t + i)}")
+                for i in range(8):
+                    e.raw(f"v_accvgpr_write_b32 {ar(ACC(db, qb) + v0 + i)}, {vr(t + i)}")
+        for i in range(4):                                   # pending packed P values: m = 1
+            pr = P16(pbuf, qb, 1) + i
+            e.raw(f"v_lshlrev_b32 {vr(t)}, 16, {vr(pr)}")
+            e.raw(f"v_and_b32 {vr(t + 1)}, 0xffff0000, {vr(pr)}")
+            e.raw(f"v_mul_f32 {vr(t)}, {vr(alpha[qb])}, {vr(t)}")
+            e.raw(f"v_mul_f32 {vr(t + 1)}, {vr(alpha[qb])}, {vr(t + 1)}")
+            e.raw(f"v_cvt_pk_bf16_f32 {vr(pr)}, {vr(t)}, {vr(t + 1)}")
+    e.raw("s_nop 3")
+    e.raw(f"s_setpc_b64 {sr(T_RET, 2)}")
+
+
+def gen_dma(e, stage):
+    for j in range(4):
+        e.raw(f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}")
+        e.raw("s_nop 0")
+        e.raw(f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}")
+        e.raw(f"s_add_u32 m0, {sr(T_M0)}, {VT(stage) + 4096 * j}")
+        e.raw("s_nop 0")
+        e.raw(f"global_load_lds_dwordx4 {vr(VOFF + j)}, {sr(D_VPTR, 2)}")
+    l_skip, l_next = e.label("skip"), e.label("nextchunk")
+    e.raw(f"s_add_u32 {sr(T_X)}, {sr(D_IDX)}, 1")
+    e.raw(f"s_cmp_ge_u32 {sr(T_X)}, {sr(S_NT)}")
+    e.raw(f"s_cbranch_scc1 {l_skip}")
+    e.raw(f"s_mov_b32 {sr(D_IDX)}, {sr(T_X)}")
+    e.raw(f"s_sub_u32 {sr(D_LEFT)}, {sr(D_LEFT)}, 1")
+    e.raw(f"s_cmp_eq_u32 {sr(D_LEFT)}, 0")
+    e.raw(f"s_cbranch_scc1 {l_next}")
+    e.raw(f"s_add_u32 {sr(D_KPTR)}, {sr(D_KPTR)}, {sr(S_KTILE)}")
+    e.raw(f"s_addc_u32 {sr(D_KPTR + 1)}, {sr(D_KPTR + 1)}, 0")
+    e.raw(f"s_add_u32 {sr(D_VPTR)}, {sr(D_VPTR)}, {sr(S_VTILE)}")
+    e.raw(f"s_addc_u32 {sr(D_VPTR + 1)}, {sr(D_VPTR + 1)}, 0")
+    e.raw(f"s_branch {l_skip}")
+    e.raw(l_next + ":")
+    gen_table_entry(e)
+    e.raw(l_skip + ":")
+
+
+def gen_table_entry(e):
+    e.raw(f"v_mov_b32 {vr(TMP)}, {sr(D_TBL)}")
+    e.raw(f"ds_read_b128 {vr(TMP + 2, 4)}, {vr(TMP)}")
+    e.raw(f"ds_read_b32 {vr(TMP + 6)}, {vr(TMP)} offset:16")
+    e.raw("s_waitcnt lgkmcnt(0)")
+    for i, dst in enumerate((D_KPTR, D_KPTR + 1, D_VPTR, D_VPTR + 1, D_LEFT)):
+        e.raw(f"v_readfirstlane_b32 {sr(dst)}, {vr(TMP + 2 + i)}")
+    e.raw(f"s_add_u32 {sr(D_TBL)}, {sr(D_TBL)}, 32")
+
+
+def generate():
+    e = Emitter()
+    p = Pipe(e)
+    l_rare = [e.label("rescale0"), e.label("rescale1")]
+    e.comment("---- prologue")
+    e.raw(f"s_lshl_b32 {sr(T_M0)}, {sr(S_WAVE)}, 10")
+    e.raw(f"s_add_u32 {sr(T_M0)}, {sr(T_M0)}, {sr(S_LDS)}")
+    e.raw(f"s_mov_b32 {sr(T_REM)}, {sr(S_NT)}")
+    e.raw(f"s_mov_b32 {sr(D_IDX)}, 0")
+    e.raw(f"s_mov_b32 {sr(D_TBL)}, {sr(S_TBL)}")
+    for b in range(2):          # addresses of the two rescale routines
+        l_here = e.label("here")
+        e.raw(f"s_getpc_b64 {sr(T_RARE + 2 * b, 2)}")
+        e.raw(l_here + ":")
+        e.raw(f"s_add_u32 {sr(T_RARE + 2 * b)}, {sr(T_RARE + 2 * b)}, {l_rare[b]}-{l_here}")
+        e.raw(f"s_addc_u32 {sr(T_RARE + 2 * b + 1)}, {sr(T_RARE + 2 * b + 1)}, 0")
+    e.raw(f"v_mov_b32 {vr(TMP)}, 0x3fb8aa3b")
+    e.raw(f"v_mul_f32 {vr(TMP)}, {sr(S_SCALE)}, {vr(TMP)}")
+    e.raw("s_nop 0")
+    e.raw(f"v_readfirstlane_b32 {sr(S_CEXP)}, {vr(TMP)}")
+    e.raw(f"v_mov_b32 {vr(ONES)}, 0x3f803f80")
+    e.raw(f"v_mov_b32 {vr(GAPR)}, {GAP}")
+    e.raw(f"v_mov_b32 {vr(KOFF)}, {vr(I_KOFF0)}")
+    e.raw(f"v_mov_b32 {vr(VOFF)}, {vr(I_VOFF0)}")
+    e.raw(f"v_mov_b32 {vr(OOFF)}, {vr(I_OOFF)}")
+    e.raw(f"v_mov_b32 {vr(LSEOFF)}, {vr(I_LSEOFF)}")
+    for j in range(1, 4):
+        e.raw(f"v_add_u32 {vr(KOFF + j)}, {sr(S_KRS16)}, {vr(KOFF + j - 1)}")
+        e.raw(f"v_add_u32 {vr(VOFF + j)}, {sr(S_VRS16)}, {vr(VOFF + j - 1)}")
+    gen_table_entry(e)
+    for st in range(3):
+        gen_dma(e, st)
+    e.comment("Q fragments (B operands) -> AGPRs; lane = query column, elements 16 ks + 8 (lane / 32) .. + 7")
+    for qb, qrow in enumerate((I_QROW0, I_QROW1)):
+        for ks in range(KS):
+            e.raw(f"global_load_dwordx4 {vr(4 * (8 * qb + ks), 4)}, {vr(qrow, 2)}, off offset:{32 * ks}")
+    for ks in range(KS):
+        e.raw(f"v_xor_b32 {vr(TMP)}, {32 * ks}, {vr(I_GF16)}")
+        e.raw(f"v_add_u32 {vr(XL + ks)}, {vr(I_XBASE)}, {vr(TMP)}")
+        e.raw(f"v_add_u32 {vr(XH + ks)}, 0x10000, {vr(XL + ks)}")
+    for db in range(DB):
+        e.raw(f"v_xor_b32 {vr(TMP)}, {64 * db}, {vr(I_LF16)}")
+        e.raw(f"v_add_u32 {vr(TRLO_L + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
+        e.raw(f"v_xor_b32 {vr(TMP)}, {(64 * db) ^ 32}, {vr(I_LF16)}")
+        e.raw(f"v_add_u32 {vr(TRHI_L + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
+        e.raw(f"v_add_u32 {vr(TRHI_L + db)}, 2048, {vr(TRHI_L + db)}")
+        e.raw(f"v_add_u32 {vr(TRLO_H + db)}, 0x10000, {vr(TRLO_L + db)}")
+        e.raw(f"v_add_u32 {vr(TRHI_H + db)}, 0x10000, {vr(TRHI_L + db)}")
+    for i in range(128):
+        e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
+    for qb in range(QB):
+        for m in range(2):
+            e.raw(f"v_mov_b32 {vr(LSUM(qb, m))}, 0")
+    e.raw("s_waitcnt vmcnt(0)")
+    for i in range(64):
+        e.raw(f"v_accvgpr_write_b32 {ar(128 + i)}, {vr(i)}")
+    e.raw("s_barrier")
+
+    e.comment("---- pipeline fill: S^T of blocks (0,0) and (0,1); reference, P and row sums of block (0,0)")
+    for blk, buf, seq in (((0, 0), 0, -2), ((0, 1), 1, -1)):
+        for ks in range(KS):
+            read_k(p, blk, ks, seq)
+            if ks % 4 == 3:
+                for k2 in range(ks - 3, ks + 1):
+                    e.need(f"k{seq}_{k2}")
+                    for qb in range(QB):
+                        d = vr(SBUF(buf, qb), 16)
+                        e.mfma(d, vr(p.use(f"k{seq}_{k2}"), 4), ar(QF(qb, k2), 4), "0" if k2 == 0 else d)
+    e.raw("s_nop 7")
+    e.raw("s_nop 7")
+    e.raw(f"v_mov_b32 {vr(NL(0))}, 0")
+    e.raw(f"v_mov_b32 {vr(NL(1))}, 0")
+    for ln in valu_max(0):                      # with r = 0: d = max * c
+        e.raw(ln)
+    for qb in range(QB):                        # reference = ceil(max * c), whole log2 units
+        e.raw(f"v_ceil_f32 {vr(MX(qb))}, {vr(MX(qb))}")
+        e.raw(f"v_sub_f32 {vr(NL(qb))}, 0, {vr(MX(qb))}")
+    for text, writes, _ in valu_exp(0, 0):
+        e.valu(text, writes)
+    for db in range(2):
+        read_vt(p, (0, 0), 0, db, 0)
+
+    l_loop, l_done = e.label("loop"), e.label("done")
+    e.raw(l_loop + ":")
+    loop_entry = list(e.ds)
+    drains = []
+    seq = 0
+    leftover = 0
+    for u in range(NS):
+        un = (u + 1) % NS
+        l_drain = e.label("drain")
+        e.raw(f"s_cmp_eq_u32 {sr(T_REM)}, 1")
+        e.raw(f"s_cbranch_scc1 {l_drain}")
+        drains.append((l_drain, u, p.snapshot(), seq))
+
+        def head(u=u):
+            # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: request tile T + 3
+            e.raw("s_waitcnt vmcnt(8)")
+            e.raw("s_barrier")
+            gen_dma(e, (u + 3) % NS)
+        leftover += gen_iter(p, (u, 0), (u, 1), (un, 0), 0, seq, head=head)
+        seq += 1
+        leftover += gen_iter(p, (u, 1), (un, 0), (un, 1), 1, seq)
+        seq += 1
+        e.raw(f"s_sub_u32 {sr(T_REM)}, {sr(T_REM)}, 1")
+    assert [t.split("_", 1)[1] for t in e.ds] == [t.split("_", 1)[1] for t in loop_entry], (e.ds, loop_entry)
+    e.raw(f"s_branch {l_loop}")
+    for l_drain, u, snap, sq in drains:
+        e.raw(l_drain + ":")
+        p.restore(snap)
+        # the last tile: its second block still needs its softmax, nothing beyond it exists
+        gen_iter(p, (u, 0), (u, 1), None, 0, sq, do_a=False)
+        e.raw("s_nop 7")                 # the exponentials above were not hidden under a second MFMA group
+        gen_iter(p, (u, 1), None, None, 1, sq + 1, do_a=False, do_valu=False, prefetch=False)
+        e.raw(f"s_branch {l_done}")
+    for b in range(2):
+        e.raw(l_rare[b] + ":")
+        gen_rescale_routine(e, b)
+    e.raw(l_done + ":")
+    e.raw("s_waitcnt vmcnt(0) lgkmcnt(0)")
+
+    e.comment("---- epilogue: O = acc / l, lse = (log2(l) + r) ln 2; lane = query row, 4 consecutive d per 16-byte store")
+    e.raw("s_nop 7")
+    e.raw("s_nop 7")
+    for qb in range(QB):
+        l, t = TMP, TMP + 1
+        e.raw(f"v_add_f32 {vr(l)}, {vr(LSUM(qb, 0))}, {vr(LSUM(qb, 1))}")
+        e.raw(f"v_mov_b32 {vr(t)}, {vr(l)}")
+        e.raw("s_nop 1")
+        e.raw(f"v_permlane32_swap_b32 {vr(t)}, {vr(l)}")
+        e.raw("s_nop 1")
+        e.raw(f"v_add_f32 {vr(l)}, {vr(l)}, {vr(t)}")
+        e.raw(f"v_rcp_f32 {vr(TMP + 2)}, {vr(l)}")
+        e.raw(f"v_log_f32 {vr(TMP + 3)}, {vr(l)}")
+        e.raw("s_nop 1")
+        e.raw(f"v_sub_f32 {vr(TMP + 3)}, {vr(TMP + 3)}, {vr(NL(qb))}")
+        e.raw(f"v_mul_f32 {vr(TMP + 3)}, 0x3f317218, {vr(TMP + 3)}")
+        if qb == 1:
+            e.raw(f"v_add_u32 {vr(OOFF)}, {sr(S_OQB)}, {vr(OOFF)}")
+            e.raw(f"v_add_u32 {vr(LSEOFF)}, 128, {vr(LSEOFF)}")
+        for db in range(DB):
+            for j in range(4):
+                t0 = 4 * (4 * db + j)
+                for i in range(4):
+                    e.raw(f"v_accvgpr_read_b32 {vr(t0 + i)}, {ar(ACC(db, qb) + 4 * j + i)}")
+                e.raw("s_nop 0")
+                for i in range(4):
+                    e.raw(f"v_mul_f32 {vr(t0 + i)}, {vr(TMP + 2)}, {vr(t0 + i)}")
+                e.raw(f"global_store_dwordx4 {vr(OOFF)}, {vr(t0, 4)}, {sr(S_OPTR, 2)} offset:{128 * db + 32 * j}")
+        # lse: one lane per row (the lower half of the wavefront)
+        e.raw(f"s_mov_b64 exec, 0xffffffff")
+        e.raw(f"global_store_dword {vr(LSEOFF)}, {vr(TMP + 3)}, {sr(S_LSEPTR, 2)}")
+        e.raw(f"s_mov_b64 exec, -1")
+        e.raw("s_waitcnt vmcnt(0)")
+    return e, leftover
+
+
+def main():
+    e, leftover = generate()
+    if leftover:
+        sys.stderr.write(f"gen_fwd_asm: {leftover} VALU instructions did not fit under the MFMAs\n")
+    clob = [f"v{i}" for i in range(256) if not 224 <= i < 240] + [f"a{i}" for i in range(256)]
+    clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 82)]
+    write_inc(sys.stdout, "gen_fwd_asm.py", "ST_FWD_FAST", e, LDS_BYTES, clob)
+
+
+if __name__ == "__main__":
+    main()

@@ -100,8 +100,18 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     const int nv = visible_keys(s.causal, s.Sk, s.q_offset + wg_last_row, a.t.k_offset[c]);
     return (nv + kBN - 1) / kBN;
   };
+  // first tile of a chunk that is this kernel's: the leading ones may belong to the fast kernel, whose
+  // partial (O, lse) is then already in the output buffers and is merged with this kernel's in the epilogue
+  const int fast_row0 = qt * kBM / kQTileFastRows * kQTileFastRows;
+  const bool fast_on = a.fwd_fast && kBN == kQTileFastKeys && fast_row0 + kQTileFastRows <= s.Sq;
+  auto chunk_t0 = [&](int c) -> int {
+    return fast_on ? qtile_fast_tiles(s.causal, s.Sk, s.q_offset, fast_row0, a.t.k_offset[c]) : 0;
+  };
+  bool fast_wrote = false;
+  if (fast_on)
+    for (int c = 0; c < a.t.n; ++c) fast_wrote = fast_wrote || chunk_t0(c) > 0;
   int c_cur = 0, t_cur = 0, n_cur = 0;          // current chunk, tile, tiles in chunk
-  while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) == 0) ++c_cur;
+  while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) <= (t_cur = chunk_t0(c_cur))) ++c_cur;
 
   auto issue_load = [&](int c, int t, int stage) {
     const char* kb = (const char*)a.t.k[c] + ((int64_t)b * a.t.ksb + (int64_t)hk * a.t.ksh) * 2;
@@ -111,16 +121,15 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   };
 
   int buf = 0;
-  if (c_cur < a.t.n) issue_load(c_cur, 0, 0);
+  if (c_cur < a.t.n) issue_load(c_cur, t_cur, 0);
   __syncthreads();
 
   while (c_cur < a.t.n) {
     // next (chunk, tile)
     int c_nxt = c_cur, t_nxt = t_cur + 1, n_nxt = n_cur;
     if (t_nxt >= n_cur) {
-      t_nxt = 0;
       ++c_nxt;
-      while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) == 0) ++c_nxt;
+      while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) <= (t_nxt = chunk_t0(c_nxt))) ++c_nxt;
     }
     const bool have_next = c_nxt < a.t.n;
     if (have_next) issue_load(c_nxt, t_nxt, buf ^ 1);
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     n_cur = n_nxt;
   }
 
-  // ---- epilogue: O = acc / l, lse = m * scale + ln(l)
+  // ---- epilogue: O = acc / l, lse = m * scale + ln(l); folded into the fast kernel's partial result if there is one
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = q_row0 + 32 * qb + r;
@@ -240,23 +249,44 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     const float inv = l > 0.f ? 1.f / l : 0.f;
     if (i < s.Sq) {
       const int64_t orow = (((int64_t)b * s.Sq + i) * s.Hq + h) * D;
+      const int64_t srow = ((int64_t)b * s.Hq + h) * s.Sq + i;
+      float lse_own = l > 0.f ? m_run[qb] * s.scale + logf(l) : -INFINITY;
+      float w_own = inv, w_prev = 0.f;          // weights of this kernel's accumulator and of the stored partial O
+      if (fast_wrote) {
+        const float lse_prev = a.lse[srow];
+        const float mx = fmaxf(lse_prev, lse_own);
+        if (mx != -INFINITY) {
+          const float e_prev = expf(lse_prev - mx), e_own = expf(lse_own - mx);
+          const float tot = e_prev + e_own;
+          w_prev = e_prev / tot;
+          w_own = inv * (e_own / tot);
+          lse_own = mx + logf(tot);
+        }
+      }
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const int d = 32 * db + 8 * q4 + 4 * g;
           float4 o;
-          o.x = acc_o[db][qb][4 * q4 + 0] * inv;
-          o.y = acc_o[db][qb][4 * q4 + 1] * inv;
-          o.z = acc_o[db][qb][4 * q4 + 2] * inv;
-          o.w = acc_o[db][qb][4 * q4 + 3] * inv;
+          o.x = acc_o[db][qb][4 * q4 + 0] * w_own;
+          o.y = acc_o[db][qb][4 * q4 + 1] * w_own;
+          o.z = acc_o[db][qb][4 * q4 + 2] * w_own;
+          o.w = acc_o[db][qb][4 * q4 + 3] * w_own;
+          if (fast_wrote) {
+            const float4 p = *reinterpret_cast<const float4*>(a.o + orow + d);
+            o.x = fmaf(p.x, w_prev, o.x);
+            o.y = fmaf(p.y, w_prev, o.y);
+            o.z = fmaf(p.z, w_prev, o.z);
+            o.w = fmaf(p.w, w_prev, o.w);
+          }
           *reinterpret_cast<float4*>(a.o + orow + d) = o;
           if (a.o_lowp) {
             uint2 w = make_uint2(pack_bf16(o.x, o.y), pack_bf16(o.z, o.w));
             *reinterpret_cast<uint2*>((uint16_t*)a.o_lowp + orow + d) = w;
           }
         }
-      if (g == 0) a.lse[((int64_t)b * s.Hq + h) * s.Sq + i] = l > 0.f ? m_run[qb] * s.scale + logf(l) : -INFINITY;
+      if (g == 0) a.lse[srow] = lse_own;
     }
   }
 }
@@ -673,7 +703,7 @@ hipError_t launch_fwd_bf16_wq(const FwdArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
+hipError_t launch_fwd_bf16(const FwdArgs& a_in, hipStream_t stream) {
   // tuning override: ST_FWD_WQ=64 selects one wavefront per SIMD with 64 queries each
   static const int wq = [] {
     const char* e = getenv("ST_FWD_WQ");
@@ -683,6 +713,25 @@ hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t stream) {
     const char* e = getenv("ST_FWD_PIPE");
     return e ? atoi(e) : 1;
   }();
+  // tuning / debugging override: ST_FWD_FAST=0 keeps the whole walk in the general kernels
+  static const int fast_env = [] {
+    const char* e = getenv("ST_FWD_FAST");
+    return e ? atoi(e) : 1;
+  }();
+  if (fast_env && fwd_fast_usable(a_in)) {
+    // fully visible full tiles by the hand-scheduled kernel, then everything else (merged into its result)
+    FwdArgs a = a_in;
+    a.fwd_fast = 1;
+    hipError_t e = launch_fwd_fast(a, stream);
+    if (e != hipSuccess) return e;
+    ProfScope prof("fwd_edge", stream);
+    const int n_qt = (a.s.Sq + 127) / 128;
+    const int64_t total = (int64_t)n_qt * a.s.Hq * a.s.B;
+    if (total > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((fwd_bf16_kernel<128, 32>), dim3((unsigned)total), dim3(256), 0, stream, a);
+    return hipGetLastError();
+  }
+  const FwdArgs& a = a_in;
   if (pipe) return launch_fwd_pipe(a, stream);
   return wq == 64 ? launch_fwd_bf16_wq<64>(a, stream) : launch_fwd_bf16_wq<32>(a, stream);
 }

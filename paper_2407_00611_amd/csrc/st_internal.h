@@ -39,6 +39,7 @@ struct FwdArgs {
   float* o;        // fp32 [B,Sq,Hq,D]
   float* lse;      // fp32 [B,Hq,Sq]
   void* o_lowp;    // nullable, [B,Sq,Hq,D] in the storage dtype
+  int32_t fwd_fast;  // 1: the fast forward kernel ran first and owns the tiles qtile_fast_tiles describes
 };
 
 struct BwdArgs {
@@ -76,23 +77,31 @@ struct ProfScope {
   hipStream_t stream;
 };
 
-// Split of the dQ work (head_dim 128): for every FULL tile of kDqFastRows queries the fast kernel takes,
-// of each chunk, the leading kDqFastKeys-key tiles that the tile's first row (hence every row) sees in full.
-constexpr int kDqFastRows = 256;
-constexpr int kDqFastKeys = 64;
-__host__ __device__ inline int dq_fast_tiles(int causal, int Sk, int64_t q_offset, int row0, int64_t k0) {
+// Split of the query-stationary kernels (forward, dQ; head_dim 128): for every FULL tile of kQTileFastRows
+// queries the fast kernel takes, of each chunk, the leading kQTileFastKeys-key tiles that the tile's first
+// row (hence every row) sees in full.
+constexpr int kQTileFastRows = 256;
+constexpr int kQTileFastKeys = 64;
+constexpr int kDqFastRows = kQTileFastRows;
+constexpr int kDqFastKeys = kQTileFastKeys;
+__host__ __device__ inline int qtile_fast_tiles(int causal, int Sk, int64_t q_offset, int row0, int64_t k0) {
   int64_t nv = Sk;
   if (causal) {
     nv = q_offset + row0 - k0 + 1;
     nv = nv < 0 ? 0 : (nv > Sk ? Sk : nv);
   }
-  return (int)(nv / kDqFastKeys);
+  return (int)(nv / kQTileFastKeys);
+}
+__host__ __device__ inline int dq_fast_tiles(int causal, int Sk, int64_t q_offset, int row0, int64_t k0) {
+  return qtile_fast_tiles(causal, Sk, q_offset, row0, k0);
 }
 
 // ---- launchers (each returns hipGetLastError() after the launch) ----
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
+bool fwd_fast_usable(const FwdArgs& a);
+hipError_t launch_fwd_fast(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
 bool dkv_fast_usable(const BwdArgs& a);
 hipError_t launch_bwd_dkv_fast(const BwdArgs& a, hipStream_t s);

@@ -46,6 +46,7 @@ class Workload:
     ring_P: int = 0          # ring size for the visit order (0: natural order)
     ring_C: int = 1          # team size of the concentric layout
     ring_rank: int = 0
+    k_ramp: float = 0.0      # K chunk j is scaled by 1 + k_ramp * j: later chunks raise the row maxima sharply
 
     @property
     def scale(self) -> float:
@@ -138,7 +139,8 @@ def chunk_seed(cfg: int, tensor_id: int, chunk: int) -> int:
 
 def make_chunk(w: Workload, tensor_id: int, j: int, keep_f32: bool = True):
     """K (tensor_id=1) or V (2) chunk j: (fp32 storage-exact values or None, bits or None)."""
-    x = normal_f32(chunk_seed(w.cfg, tensor_id, j), (w.B, w.Sk, w.Hkv, w.D), w.sigma)
+    sigma = w.sigma * (1.0 + w.k_ramp * j) if tensor_id == TENSOR_K else w.sigma
+    x = normal_f32(chunk_seed(w.cfg, tensor_id, j), (w.B, w.Sk, w.Hkv, w.D), sigma)
     f, bits = _store(x, w.dtype)
     return (f if keep_f32 or bits is None else None), bits
 

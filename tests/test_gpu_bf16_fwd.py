@@ -19,12 +19,34 @@ STEP_CASES = [
     ("ragged_causal_d64", 2, 3, 1, 64, 260, 150, 2, 40, True),
     ("noncausal_d64", 1, 4, 4, 64, 515, 64, 3, 0, False),
     ("one_row_one_key", 1, 1, 1, 128, 1, 1, 1, 0, True),
+    # full 256-query tiles: the hand-scheduled loop takes the fully visible 64-key tiles, the general kernel the rest
+    ("fast_one_tile", 1, 1, 1, 128, 256, 64, 1, 0, False),
+    ("fast_two_tiles", 1, 1, 1, 128, 256, 128, 1, 0, False),
+    ("fast_chunk_switches", 2, 4, 2, 128, 300, 320, 3, 0, False),
+    ("fast_causal_mix", 1, 2, 1, 128, 512, 200, 5, 520, True),
 ]
 
 
 def _workload(c):
     name, B, Hq, Hkv, D, Sq, Sk, n, q0, causal = c
     return si.Workload(name, 80 + len(name), "bf16", B, Hq, Hkv, D, Sq, Sk, n, q0, causal, False)
+
+
+def test_ring_forward_rising_maxima():
+    """Keys grow from chunk to chunk, so the row maxima jump by far more than the lazy reference tolerates:
+    the rescale routine of the hand-scheduled loop runs several times per row."""
+    w = si.Workload("fast_rescale", 86, "bf16", 1, 2, 1, 128, 256, 192, 5, 5 * 192 - 256, True, False, k_ramp=2.0)
+    inp = si.make_inputs(w)
+    q, ks, vs, _ = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    for order in ([0, 1, 2, 3, 4], [4, 0, 3, 1, 2]):
+        print(f"[fast_rescale] order {order}", flush=True)
+        o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, st.ST_RING_FUSED)
+        assert_close(host(o), o_ref, "bf16", "o")
+        assert_close(host(lse), lse_ref, "bf16", "lse", lse=True)
+        assert_close(host(o_low), o_ref, "bf16", "o bf16")
 
 
 @pytest.mark.parametrize("case", STEP_CASES, ids=[c[0] for c in STEP_CASES])
