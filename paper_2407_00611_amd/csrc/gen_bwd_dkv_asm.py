@@ -19,9 +19,15 @@ to the general kernel).  Per block and wavefront, with the MFMA C layout "lane =
               VALU: dS = P dP', bf16 pack (in place)                   (runs under phase 3 / 4 MFMAs)
     phase 4   dK^T += Q^T dS                    A: Q^T by LDS transpose reads,  B: packed dS
 Q / dO tiles arrive by direct global->LDS loads into a 4-stage ring, three blocks ahead; the per-row
-statistics (lse, Delta) are loaded two blocks ahead into registers, transformed once and written to LDS
+statistics (lse, Delta) are loaded three blocks ahead into registers, transformed once and written to LDS
 by every wavefront (identical values), so that no per-element VALU work is spent on them.
+
+One barrier per block, in the middle of it (between phase 2 and phase 3): it publishes the next block's
+tile and statistics and frees the stage of the block before, so the first LDS reads of the next block
+are issued at the tail of this one and the MFMA stream runs across block boundaries.  The bookkeeping
+of the four global pointers is branch-free scalar code spread under the MFMAs of phase 4.
 """
+import os
 import sys
 
 from st_asmgen import Emitter, ar, sr, vr, write_inc
@@ -39,12 +45,13 @@ def KF(nb, ks): return 4 * (8 * nb + ks)            # v[KF : KF+3]
 S0 = 64                                              # S[nb][v]  = v[64 + 16 nb + v]   (later P, fp32)
 DP0 = 96                                             # dP[nb][v] = v[96 + 16 nb + v]   (later dS, then packed dS)
 P16 = 128                                            # P16[nb][m] = v[128 + 8 nb + 4 m : +3]
+ND = 128                                             # nd[v] = -Delta(row v): shares registers with P16 (dead from slot 18 on,
+                                                     # P16 is first written later and last read in phase 3; nd is re-read at the tail)
 NL = 144                                             # nl[v] = -lse(row v) * log2e
-ND = 160                                             # nd[v] = -Delta(row v)
-POOL0, NPOOL = 176, 10                               # fragment pool, 4 registers each
-ST = 216                                             # ST + 2 set + {0: lse, 1: Delta}
-TMP = 220                                            # 220..222 temporaries, 223 = -inf
-NINF = 223
+POOL0, NPOOL = 160, 12                               # fragment pool, 4 registers each; 48 fragments per block
+ST = 208                                             # ST + 2 set + {0: lse, 1: Delta}
+TMP = 212                                            # 212..214 temporaries, 215 = -inf
+NINF = 215
 X = 224                                              # x[ks]: natural-read offset inside a Q / dO tile
 XV = 232                                             # xv[ks]: the same inside this wavefront's V rows
 TRLO, TRHI = 240, 244                                # transpose-read offsets per d block
@@ -62,7 +69,7 @@ S_VPTR, S_VRS16, S_LDS, S_DKPTR, S_DVPTR, S_WAVE, S_RS32, S_SCALE = 48, 50, 51, 
 # scalar temporaries (clobbered)
 T_QPTR, T_QHEAD, T_DOPTR, T_DOHEAD = 64, 66, 68, 70
 T_LSEPTR, T_LSEHEAD, T_DLPTR, T_DLHEAD = 72, 74, 76, 78
-T_DBLK, T_DSTEP, T_SBLK, T_SSTEP, T_REM, T_M0, T_HIMASK, T_X, T_VPTR = 80, 81, 82, 83, 84, 85, 86, 88, 90
+T_DBLK, T_DSTEP, T_ADV, T_WRAP, T_REM, T_M0, T_HIMASK, T_X, T_VPTR, T_INC, T_HINC = 80, 81, 82, 83, 84, 85, 86, 88, 90, 92, 93
 
 def ACC_K(db, nb): return 16 * (2 * db + nb)
 def ACC_V(db, nb): return 128 + 16 * (2 * db + nb)
@@ -74,66 +81,99 @@ def DOT(s): return 1024 + 16384 * s + 8192
 VT = 1024 + 16384 * NS                               # 256 x 128 bf16 V tile (64 KiB)
 LDS_BYTES = VT + 65536
 
-LAT = 3          # MFMA slots between the issue of an LDS read and its first use
-BUDGET = 6       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
+LAT = int(os.environ.get("ST_GEN_DKV_LAT", 3))          # MFMA slots between the issue of an LDS read and its first use
+BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6))       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
 
 
-def gen_step(e: Emitter, u: int):
-    """One 32-query block on LDS stage u (the loop is unrolled NS times so that stage addresses are immediates)."""
-    s = u
-    qt, dot_, stats = QT(s), DOT(s), STATS + 256 * s
-    e.comment(f"================ block on stage {s}")
 
-    # ---- DMA of the tile PF blocks ahead into stage (u + PF) % NS, statistics of the block 2 ahead
-    sd = (u + PF) % NS
-    for tname, ptr, off, tbase in (("q", T_QPTR, QOFF, QT(sd)), ("do", T_DOPTR, DOOFF, DOT(sd))):
+STREAMS = ((T_QPTR, T_QHEAD, S_QBS, S_QHS), (T_DOPTR, T_DOHEAD, S_DOBS, S_DOHS),
+           (T_LSEPTR, T_LSEHEAD, None, S_STATHS), (T_DLPTR, T_DLHEAD, None, S_STATHS))
+
+
+def advance_code():
+    """Branch-free move of the four global streams (Q, dO, lse, Delta) to the next block; they stay on the
+    last block once all of them have been requested.  Only these instructions (and the loop control behind
+    them) touch SCC between them, so they may be spread among non-scalar instructions."""
+    c = [f"s_add_u32 {sr(T_X)}, {sr(T_DSTEP)}, 1",
+         f"s_cmp_lt_u32 {sr(T_X)}, {sr(S_NSTEPS)}",
+         f"s_cselect_b32 {sr(T_DSTEP)}, {sr(T_X)}, {sr(T_DSTEP)}",
+         f"s_cselect_b32 {sr(T_ADV)}, 1, 0",
+         f"s_add_u32 {sr(T_X)}, {sr(T_DBLK)}, {sr(T_ADV)}",
+         f"s_cmp_eq_u32 {sr(T_X)}, {sr(S_NBLK)}",                       # only possible when advancing
+         f"s_cselect_b32 {sr(T_DBLK)}, 0, {sr(T_X)}",
+         f"s_cselect_b32 {sr(T_WRAP)}, -1, 0"]
+    for ptr, head, bs, hs in STREAMS:
+        c.append(f"s_mul_i32 {sr(T_INC)}, {sr(T_ADV)}, {sr(bs)}" if bs is not None else f"s_lshl_b32 {sr(T_INC)}, {sr(T_ADV)}, 7")
+        c.append(f"s_and_b32 {sr(T_HINC)}, {sr(T_WRAP)}, {sr(hs)}")
+        c += [f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(T_INC)}", f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0",
+              f"s_add_u32 {sr(head)}, {sr(head)}, {sr(T_HINC)}", f"s_addc_u32 {sr(head + 1)}, {sr(head + 1)}, 0"]
+    c.append(f"s_cmp_lg_u32 {sr(T_WRAP)}, 0")
+    for ptr, head, bs, hs in STREAMS:
+        c.append(f"s_cselect_b64 {sr(ptr, 2)}, {sr(head, 2)}, {sr(ptr, 2)}")
+    return c
+
+
+def request_code(stage, st_set):
+    """Statistics of a block into register set st_set, its Q / dO tile into LDS stage `stage` (6 memory operations)."""
+    c = [[f"global_load_dword {vr(ST + 2 * st_set)}, {vr(STAT_G)}, {sr(T_LSEPTR, 2)}",
+          f"global_load_dword {vr(ST + 2 * st_set + 1)}, {vr(STAT_G)}, {sr(T_DLPTR, 2)}"]]
+    for ptr, off, tbase in ((T_QPTR, QOFF, QT(stage)), (T_DOPTR, DOOFF, DOT(stage))):
         for j in range(2):
-            e.raw(f"s_add_u32 m0, {sr(T_M0)}, {tbase + 4096 * j}")
-            e.raw("s_nop 0")
-            e.raw(f"global_load_lds_dwordx4 {vr(off + j)}, {sr(ptr, 2)}")
-    st_set = u % 2
-    e.raw(f"global_load_dword {vr(ST + 2 * st_set)}, {vr(STAT_G)}, {sr(T_LSEPTR, 2)}")
-    e.raw(f"global_load_dword {vr(ST + 2 * st_set + 1)}, {vr(STAT_G)}, {sr(T_DLPTR, 2)}")
-    gen_advance(e, T_DSTEP, T_DBLK, [(T_QPTR, T_QHEAD, S_QBS, S_QHS), (T_DOPTR, T_DOHEAD, S_DOBS, S_DOHS)])
-    gen_advance(e, T_SSTEP, T_SBLK, [(T_LSEPTR, T_LSEHEAD, None, S_STATHS), (T_DLPTR, T_DLHEAD, None, S_STATHS)])
+            c.append([f"s_add_u32 m0, {sr(T_M0)}, {tbase + 4096 * j}", "s_nop 0",
+                      f"global_load_lds_dwordx4 {vr(off + j)}, {sr(ptr, 2)}"])
+    return c
 
-    # ---- the MFMA slots of the block: (phase, operands)
-    pool_next = [0]
-    frag_reg = {}      # tag -> first register
-    frag_last_use = {}  # pool index -> instruction count at its last MFMA use
 
-    pool_owner = {}     # pool slot -> tag
-    uses_left = {}      # tag -> MFMAs that still have to read it
+def stat_publish(e, st_set, stage, tag):
+    """-lse log2(e) (or -inf for an empty row, whose P must be 0) and -Delta of the 32 rows to the stage's statistics slot."""
+    rs = ST + 2 * st_set
+    e.raw(f"v_mul_f32 {vr(TMP)}, 0xbfb8aa3b, {vr(rs)}")
+    e.raw(f"v_xor_b32 {vr(TMP + 1)}, 0x80000000, {vr(rs + 1)}")
+    e.raw(f"v_cmp_eq_f32 vcc, 0x7f800000, {vr(TMP)}")
+    e.raw("s_nop 1")
+    e.raw(f"v_cndmask_b32 {vr(TMP)}, {vr(TMP)}, {vr(NINF)}, vcc")
+    e.raw(f"v_cndmask_b32_e64 {vr(TMP)}, {vr(TMP)}, {vr(TMP + 1)}, {sr(T_HIMASK, 2)}")
+    e.ds_read(f"ds_write_b32 {vr(STAT_L)}, {vr(TMP)} offset:{STATS + 256 * stage}", tag)
 
-    def alloc(tag):
-        i = pool_next[0] % NPOOL
-        pool_next[0] += 1
-        old = pool_owner.get(i)
-        assert old is None or uses_left[old] == 0, f"fragment {old} overwritten by {tag} before its last use"
-        pool_owner[i] = tag
-        uses_left[tag] = 1 if tag.startswith("v") else NKB
-        frag_reg[tag] = POOL0 + 4 * i
+
+class Pool:
+    """Round-robin fragment registers; NPOOL divides the 48 fragments of a block, so every block sees the same map."""
+
+    def __init__(self):
+        self.next, self.owner, self.uses_left, self.reg = 0, {}, {}, {}
+
+    def alloc(self, tag, uses):
+        i = self.next % NPOOL
+        self.next += 1
+        old = self.owner.get(i)
+        assert old is None or self.uses_left[old] == 0, f"fragment {old} overwritten by {tag} before its last use"
+        self.owner[i], self.uses_left[tag], self.reg[tag] = tag, uses, POOL0 + 4 * i
         return POOL0 + 4 * i
 
-    def use(tag):
-        uses_left[tag] -= 1
-        return frag_reg[tag]
+    def use(self, tag):
+        assert self.uses_left[tag] > 0, tag
+        self.uses_left[tag] -= 1
+        return self.reg[tag]
 
-    # LDS reads by the slot after which they are issued (-1: before the first MFMA)
-    reads = {k: [] for k in range(-1, 64)}
+
+def plan_reads(e, pool, u, seq):
+    """LDS reads of the block on stage u, by the MFMA slot behind which they are issued; negative slots are
+    issued by the block before (slot + 64) or by the prologue."""
+    qt, dot_, stats = QT(u), DOT(u), STATS + 256 * u
+    reads = {k: [] for k in range(-LAT, 64)}
 
     def plan(first_use, fn):
-        reads[max(first_use - LAT, -1)].append(fn)
+        reads[first_use - LAT].append(fn)
 
-    def rd_nat(tag, tile_imm, ks, xbase=X):
+    def rd_nat(tag, tile_imm, ks, xbase, uses):
         def f():
-            r = alloc(tag)
+            r = pool.alloc(tag, uses)
             e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xbase + ks)} offset:{tile_imm}", tag)
         return f
 
     def rd_tr(tag, tile_imm, m, db):
         def f():
-            r = alloc(tag)
+            r = pool.alloc(tag, NKB)
             e.ds_read(f"ds_read_b64_tr_b16 {vr(r, 2)}, {vr(TRLO + db)} offset:{tile_imm + 4096 * m}", tag + "lo")
             e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(TRHI + db)} offset:{tile_imm + 4096 * m}", tag)
         return f
@@ -144,32 +184,45 @@ def gen_step(e: Emitter, u: int):
                 e.ds_read(f"ds_read_b128 {vr(base_reg + 4 * j, 4)}, {vr(G16)} offset:{imm + 32 * j}", f"{tag}{j}")
         return f
 
-    slots = []
-    # phase 1
     for ks in range(KS):
-        plan(2 * ks, rd_nat(f"q{ks}", qt, ks))
-        for nb in range(NKB):
-            slots.append(("S", ks, nb))
-    plan(0, rd_stat("nd", ND, stats + 128))
-    plan(1, rd_stat("nl", NL, stats))
-    # phase 2
+        plan(2 * ks, rd_nat(f"{seq}q{ks}", qt, ks, X, NKB))
+        if ks == 0:
+            plan(0, rd_stat(f"{seq}nd", ND, stats + 128))
+            plan(1, rd_stat(f"{seq}nl", NL, stats))
     for ks in range(KS):
         base = 16 + 2 * ks
-        plan(base, rd_nat(f"do{ks}", dot_, ks))
+        plan(base, rd_nat(f"{seq}do{ks}", dot_, ks, X, NKB))
         for nb in range(NKB):
-            plan(base + nb, rd_nat(f"v{nb}_{ks}", 8192 * nb, ks, XV))
-            slots.append(("dP", ks, nb))
-    # phase 3 / 4
+            plan(base + nb, rd_nat(f"{seq}v{nb}_{ks}", 8192 * nb, ks, XV, 1))
     for ph, tile in (("dV", dot_), ("dK", qt)):
         for m in range(2):
             for db in range(DB):
                 base = (32 if ph == "dV" else 48) + 2 * (4 * m + db)
-                plan(base, rd_tr(f"{ph}t{m}_{db}", tile, m, db))
+                plan(base, rd_tr(f"{seq}{ph}t{m}_{db}", tile, m, db))
+    return reads
+
+
+SYNC_SLOT = 31            # the barrier sits behind this MFMA slot (end of phase 2)
+PUBLISH_SLOT = 26         # wait for the next block's loads and write its statistics behind this slot
+
+
+def gen_step(e, pool, u, seq, reads, next_reads):
+    """One 32-query block on LDS stage u (the loop is unrolled NS times so that stage addresses are immediates)."""
+    e.comment(f"================ block on stage {u}")
+    slots = []
+    for ks in range(KS):
+        for nb in range(NKB):
+            slots.append(("S", ks, nb))
+    for ks in range(KS):
+        for nb in range(NKB):
+            slots.append(("dP", ks, nb))
+    for ph in ("dV", "dK"):
+        for m in range(2):
+            for db in range(DB):
                 for nb in range(NKB):
                     slots.append((ph, m, db, nb))
-    assert len(slots) == 64
 
-    # ---- VALU work: (earliest slot, text, registers written, issue units)
+    # ---- VALU work: (earliest slot, text, registers written, issue units, LDS tag it waits for)
     valu = []
     def S(nb, v): return S0 + 16 * nb + v
     def DP(nb, v): return DP0 + 16 * nb + v
@@ -180,14 +233,14 @@ def gen_step(e: Emitter, u: int):
             for grp in range(2):
                 vs = [8 * m + 4 * grp + i for i in range(4)]
                 for v in vs:
-                    valu.append((early, f"v_fma_f32 {vr(S(nb, v))}, {vr(S(nb, v))}, {sr(S_CEXP)}, {vr(NL + v)}", (), 1, f"nl{v // 4}"))
+                    valu.append((early, f"v_fma_f32 {vr(S(nb, v))}, {vr(S(nb, v))}, {sr(S_CEXP)}, {vr(NL + v)}", (), 1, f"{seq}nl{v // 4}"))
                 for v in vs:
                     valu.append((early, f"v_exp_f32 {vr(S(nb, v))}, {vr(S(nb, v))}", (), 2, None))
                 if grp == 1:
                     for i in range(4):
                         d = P16 + 8 * nb + 4 * m + i
                         a = S(nb, 8 * m + 2 * i)
-                        valu.append((early, f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1, None))
+                        valu.append((max(early, 20), f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1, None))
     # VALU-2: dS = P dP', packed in place.  dP[nb] is written by slot 30 + nb; same distance.
     for m in range(2):
         for nb in range(NKB):
@@ -199,128 +252,99 @@ def gen_step(e: Emitter, u: int):
                 a = DP(nb, 8 * m + 2 * i)
                 valu.append((early, f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1, None))
     vi = [0]
-    produced = {}   # register -> True once its packing instruction is out
+    produced = {}
+    cur_slot = [0]
 
     def emit_valu(item):
         _, text, writes, units, needtag = item
         if needtag:
-            e.need(needtag + "")   # statistics read (tags nl0..nl3)
+            assert cur_slot[0] < 65 - LAT, "statistics registers are reloaded for the next block at the tail"
+            e.need(needtag)
         e.valu(text, writes)
         for r in writes:
             produced[r] = True
         return units
 
     def flush_until(regs):
-        # the MFMA about to be issued reads packed registers: emit VALU work until they exist
         while not all(produced.get(r) for r in regs):
             assert vi[0] < len(valu), "packed operand never produced"
             emit_valu(valu[vi[0]])
             vi[0] += 1
 
-    for fn in reads[-1]:
-        fn()
+    # scalar / memory side work behind fixed slots
+    side = {k: [] for k in range(64)}
+    req = request_code((u + PF) % NS, (u + 1) % 2)
+    for i, grp in enumerate(req):                       # behind the barrier, one memory operation group per slot
+        side[SYNC_SLOT + 1 + i] += grp
+    adv = advance_code()
+    per = 4
+    for i in range(0, len(adv), per):                   # under phase 4, where the VALU is idle
+        side[48 + i // per] += adv[i:i + per]
+    assert 48 + (len(adv) - 1) // per < 61
+
+    stw = f"{seq}stw"
     for k, sl in enumerate(slots):
         ph = sl[0]
+        cur_slot[0] = k
         if ph == "S":
             _, ks, nb = sl
-            e.need(f"q{ks}")
+            tag = f"{seq}q{ks}"
+            e.need(tag)
             c = "0" if ks == 0 else vr(S0 + 16 * nb, 16)
-            e.mfma(vr(S0 + 16 * nb, 16), vr(use(f"q{ks}"), 4), vr(KF(nb, ks), 4), c)
+            e.mfma(vr(S0 + 16 * nb, 16), vr(pool.use(tag), 4), vr(KF(nb, ks), 4), c)
         elif ph == "dP":
             _, ks, nb = sl
-            e.need(f"do{ks}")
-            e.need(f"v{nb}_{ks}")
+            e.need(f"{seq}do{ks}")
+            e.need(f"{seq}v{nb}_{ks}")
             if ks == 0:
-                e.need("nd3")
+                e.need(f"{seq}nd3")
                 c = vr(ND, 16)
             else:
                 c = vr(DP0 + 16 * nb, 16)
-            e.mfma(vr(DP0 + 16 * nb, 16), vr(use(f"do{ks}"), 4), vr(use(f"v{nb}_{ks}"), 4), c)
+            a_reg = pool.use(f"{seq}do{ks}")
+            e.mfma(vr(DP0 + 16 * nb, 16), vr(a_reg, 4), vr(pool.use(f"{seq}v{nb}_{ks}"), 4), c)
         else:
             _, m, db, nb = sl
-            tag = f"{ph}t{m}_{db}"
+            tag = f"{seq}{ph}t{m}_{db}"
             e.need(tag)
             if ph == "dV":
                 b0, acc = P16 + 8 * nb + 4 * m, ACC_V(db, nb)
             else:
                 b0, acc = DP0 + 16 * nb + 4 * m, ACC_K(db, nb)
-            flush_until([b0 + i for i in range(4)] if ph == "dV" else [DP0 + 16 * nb + 4 * m + i for i in range(4)])
-            e.mfma(ar(acc, 16), vr(use(tag), 4), vr(b0, 4), ar(acc, 16), breads=[b0 + i for i in range(4)])
-        # side work of this slot
+            flush_until([b0 + i for i in range(4)])
+            e.mfma(ar(acc, 16), vr(pool.use(tag), 4), vr(b0, 4), ar(acc, 16), breads=[b0 + i for i in range(4)])
+        # ---- side work of this slot
         units = 0
-        for fn in reads[k]:
+        for fn in reads[k] + (next_reads[k - 64] if k - 64 in next_reads else []):
             n0 = len(e.ds)
             fn()
             units += len(e.ds) - n0
+        for ln in side[k]:
+            e.raw(ln)
+            units += 1
+        if k == PUBLISH_SLOT:
+            # tile and statistics of the next block: everything but the six newest memory operations has landed
+            e.raw("s_waitcnt vmcnt(6)")
+            stat_publish(e, (u + 1) % 2, (u + 1) % NS, stw)
+            units += 8
         while vi[0] < len(valu) and valu[vi[0]][0] <= k and units + valu[vi[0]][3] <= BUDGET:
             units += emit_valu(valu[vi[0]])
             vi[0] += 1
+        if k == SYNC_SLOT:
+            e.need(stw)
+            e.raw("s_barrier")
     assert vi[0] == len(valu), f"VALU work left over: {len(valu) - vi[0]}"
-    assert all(n == 0 for n in uses_left.values())
-
-    # ---- end of block: the next block's tiles have landed, its statistics go to LDS, everyone syncs
-    nxt = (u + 1) % NS
-    rs = ST + 2 * ((u + 1) % 2)      # statistics loaded during the previous block
-    e.raw("s_waitcnt vmcnt(6)")
-    e.valu(f"v_mul_f32 {vr(TMP)}, 0xbfb8aa3b, {vr(rs)}")               # -lse * log2(e)
-    e.valu(f"v_xor_b32 {vr(TMP + 1)}, 0x80000000, {vr(rs + 1)}")       # -Delta
-    e.valu(f"v_cmp_eq_f32 vcc, 0x7f800000, {vr(TMP)}")                 # lse = -inf (empty row): P must be 0
-    e.raw("s_nop 1")
-    e.valu(f"v_cndmask_b32 {vr(TMP)}, {vr(TMP)}, {vr(NINF)}, vcc")
-    e.valu(f"v_cndmask_b32_e64 {vr(TMP)}, {vr(TMP)}, {vr(TMP + 1)}, {sr(T_HIMASK, 2)}")
-    e.raw(f"ds_write_b32 {vr(STAT_L)}, {vr(TMP)} offset:{STATS + 256 * nxt}")
-    e.raw("s_waitcnt lgkmcnt(0)")
-    e.ds = []
-    e.raw("s_barrier")
-
-
-def gen_advance(e: Emitter, step, blk, ptrs):
-    """Move a stream of (pointer, head pointer) pairs to the next block; stays on the last block at the end."""
-    l_skip, l_wrap = e.label("skip"), e.label("wrap")
-    e.raw(f"s_add_u32 {sr(T_X)}, {sr(step)}, 1")
-    e.raw(f"s_cmp_ge_u32 {sr(T_X)}, {sr(S_NSTEPS)}")
-    e.raw(f"s_cbranch_scc1 {l_skip}")
-    e.raw(f"s_mov_b32 {sr(step)}, {sr(T_X)}")
-    e.raw(f"s_add_u32 {sr(blk)}, {sr(blk)}, 1")
-    e.raw(f"s_cmp_eq_u32 {sr(blk)}, {sr(S_NBLK)}")
-    e.raw(f"s_cbranch_scc1 {l_wrap}")
-    for ptr, head, bs, hs in ptrs:
-        inc = sr(bs) if bs is not None else "128"
-        e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {inc}")
-        e.raw(f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0")
-    e.raw(f"s_branch {l_skip}")
-    e.raw(l_wrap + ":")
-    e.raw(f"s_mov_b32 {sr(blk)}, 0")
-    for ptr, head, bs, hs in ptrs:
-        e.raw(f"s_add_u32 {sr(head)}, {sr(head)}, {sr(hs)}")
-        e.raw(f"s_addc_u32 {sr(head + 1)}, {sr(head + 1)}, 0")
-        e.raw(f"s_mov_b64 {sr(ptr, 2)}, {sr(head, 2)}")
-    e.raw(l_skip + ":")
-
-
-def gen_dma_block(e: Emitter, stage):
-    for ptr, off, tbase in ((T_QPTR, QOFF, QT(stage)), (T_DOPTR, DOOFF, DOT(stage))):
-        for j in range(2):
-            e.raw(f"s_add_u32 m0, {sr(T_M0)}, {tbase + 4096 * j}")
-            e.raw("s_nop 0")
-            e.raw(f"global_load_lds_dwordx4 {vr(off + j)}, {sr(ptr, 2)}")
-    gen_advance(e, T_DSTEP, T_DBLK, [(T_QPTR, T_QHEAD, S_QBS, S_QHS), (T_DOPTR, T_DOHEAD, S_DOBS, S_DOHS)])
-
-
-def gen_stat_load(e: Emitter, st_set):
-    e.raw(f"global_load_dword {vr(ST + 2 * st_set)}, {vr(STAT_G)}, {sr(T_LSEPTR, 2)}")
-    e.raw(f"global_load_dword {vr(ST + 2 * st_set + 1)}, {vr(STAT_G)}, {sr(T_DLPTR, 2)}")
-    gen_advance(e, T_SSTEP, T_SBLK, [(T_LSEPTR, T_LSEHEAD, None, S_STATHS), (T_DLPTR, T_DLHEAD, None, S_STATHS)])
 
 
 def generate():
     e = Emitter()
+    pool = Pool()
     e.comment("---- prologue: stream state")
     for t, s_ in ((T_QPTR, S_QPTR), (T_QHEAD, S_QPTR), (T_DOPTR, S_DOPTR), (T_DOHEAD, S_DOPTR),
                   (T_LSEPTR, S_LSEPTR), (T_LSEHEAD, S_LSEPTR), (T_DLPTR, S_DLPTR), (T_DLHEAD, S_DLPTR),
                   (T_VPTR, S_VPTR)):
         e.raw(f"s_mov_b64 {sr(t, 2)}, {sr(s_, 2)}")
-    for t in (T_DBLK, T_DSTEP, T_SBLK, T_SSTEP):
+    for t in (T_DBLK, T_DSTEP):
         e.raw(f"s_mov_b32 {sr(t)}, 0")
     e.raw(f"s_mov_b32 {sr(T_REM)}, {sr(S_NSTEPS)}")
     e.comment("c = scale * log2(e) (there is no scalar floating point unit)")
@@ -372,39 +396,50 @@ def generate():
         e.raw(f"v_xor_b32 {vr(TMP)}, {(64 * db) ^ 32}, {vr(I_LF16)}")
         e.raw(f"v_add_u32 {vr(TRHI + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
         e.raw(f"v_add_u32 {vr(TRHI + db)}, 2048, {vr(TRHI + db)}")
-    e.comment("---- tiles 0..2 and statistics 0..1 in flight; accumulators to zero meanwhile")
-    gen_dma_block(e, 0)
-    gen_stat_load(e, 0)          # block k's statistics travel in register set k % 2
-    gen_dma_block(e, 1)
-    gen_dma_block(e, 2)
-    gen_stat_load(e, 1)
+    e.comment("---- blocks 0 and 1 requested; accumulators to zero meanwhile")
+    for blk in range(2):
+        for grp in request_code(blk, blk):
+            for ln in grp:
+                e.raw(ln)
+        for ln in advance_code():
+            e.raw(ln)
     for i in range(256):
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
-    e.comment("statistics of block 0 to LDS stage 0")
-    e.raw("s_waitcnt vmcnt(10)")
-    rs = ST
-    e.raw(f"v_mul_f32 {vr(TMP)}, 0xbfb8aa3b, {vr(rs)}")
-    e.raw(f"v_xor_b32 {vr(TMP + 1)}, 0x80000000, {vr(rs + 1)}")
-    e.raw(f"v_cmp_eq_f32 vcc, 0x7f800000, {vr(TMP)}")
-    e.raw("s_nop 1")
-    e.raw(f"v_cndmask_b32 {vr(TMP)}, {vr(TMP)}, {vr(NINF)}, vcc")
-    e.raw(f"v_cndmask_b32_e64 {vr(TMP)}, {vr(TMP)}, {vr(TMP + 1)}, {sr(T_HIMASK, 2)}")
-    e.raw(f"ds_write_b32 {vr(STAT_L)}, {vr(TMP)} offset:{STATS}")
+    e.comment("statistics of block 0 to LDS stage 0, then block 2 requested (its statistics reuse block 0's registers)")
+    e.raw("s_waitcnt vmcnt(6)")
+    stat_publish(e, 0, 0, "stw")
     e.raw("s_waitcnt lgkmcnt(0)")
+    e.ds = []
+    for grp in request_code(2, 0):
+        for ln in grp:
+            e.raw(ln)
+    for ln in advance_code():
+        e.raw(ln)
     e.raw("s_barrier")
 
+    plans = [plan_reads(e, pool, u, u) for u in range(NS)] + [None]
+    # what block 0 of every pass through the loop expects to be in flight: its first reads
+    for k in range(-LAT, 0):
+        for fn in plans[0][k]:
+            fn()
     l_loop, l_done = e.label("loop"), e.label("done")
     e.raw(l_loop + ":")
+    entry = list(e.ds)
+    entry_next = pool.next % NPOOL
     for u in range(NS):
-        gen_step(e, u)
+        if u == NS - 1:
+            plans[NS] = plan_reads(e, pool, 0, NS)      # block 0 of the next pass
+        gen_step(e, pool, u, u, plans[u], plans[u + 1])
         e.raw(f"s_sub_u32 {sr(T_REM)}, {sr(T_REM)}, 1")
         e.raw(f"s_cmp_eq_u32 {sr(T_REM)}, 0")
         if u < NS - 1:
             e.raw(f"s_cbranch_scc1 {l_done}")
         else:
             e.raw(f"s_cbranch_scc0 {l_loop}")
+    strip = lambda tags: [t.lstrip("0123456789") for t in tags]
+    assert strip(e.ds) == strip(entry) and pool.next % NPOOL == entry_next, (e.ds, entry)
     e.raw(l_done + ":")
-    e.raw("s_waitcnt vmcnt(0)")
+    e.raw("s_waitcnt vmcnt(0) lgkmcnt(0)")
 
     e.comment("---- epilogue: dk_acc += scale * dK, dv_acc += dV; lane = key row, 4 consecutive d per 16-byte access")
     e.raw("s_nop 7")
@@ -439,7 +474,7 @@ def generate():
 def main():
     e = generate()
     clob = [f"v{i}" for i in range(256) if not (IN_V <= i < IN_V + 16)] + [f"a{i}" for i in range(256)]
-    clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 92)]
+    clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 94)]
     write_inc(sys.stdout, "gen_bwd_dkv_asm.py", "ST_DKV_FAST", e, LDS_BYTES, clob)
 
 

@@ -17,6 +17,7 @@ every VALU result is needed one group later than it is produced:
 K / V tiles (64 keys) arrive by direct global->LDS loads into a 4-stage ring, three tiles ahead; one
 barrier per tile.  The chunk table (base pointers, tiles per chunk) sits in LDS, written by the C++ side.
 """
+import os
 import sys
 
 from st_asmgen import Emitter, ar, sr, vr, write_inc
@@ -54,8 +55,8 @@ def VT(s): return 32768 * s + 16384
 TBL = 32768 * NS                                     # 64 entries x 32 bytes: k lo/hi, v lo/hi, tiles, pad
 LDS_BYTES = TBL + 2048
 
-LAT = 3
-BUDGET = 6
+LAT = int(os.environ.get("ST_GEN_DQ_LAT", 3))
+BUDGET = int(os.environ.get("ST_GEN_DQ_BUDGET", 6))
 
 
 class Pipe:

@@ -22,6 +22,7 @@ Per 32-key block i and wavefront two groups of 16 MFMAs, software-pipelined two 
 K / V tiles (64 keys) arrive by direct global->LDS loads into a 4-stage ring, three tiles ahead; one
 barrier per tile.  The chunk table (base pointers, tiles per chunk) sits in LDS, written by the C++ side.
 """
+import os
 import sys
 
 from st_asmgen import Emitter, ar, sr, vr, write_inc
@@ -62,8 +63,8 @@ def VT(s): return 32768 * s + 16384
 TBL = 32768 * NS
 LDS_BYTES = TBL + 2048
 
-LAT = 3
-BUDGET = 7
+LAT = int(os.environ.get("ST_GEN_FWD_LAT", 3))
+BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 7))
 BRANCH_SLOT = 9                                      # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
 
 
