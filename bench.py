@@ -25,6 +25,46 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk/CU x 2.4 GHz
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def hbm_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload.split('_')[0]}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def merge_pass(st, torch, w) -> dict:
+    """HBM rate of the log-sum-exp merge (st_attn_merge) at this workload's state size.  Four buffer sets are
+    rotated so that no operand of a launch is left in the 256 MB last-level cache by the launch before."""
+    sets = []
+    for _ in range(4):
+        o_a = torch.randn((w.B, w.Sq, w.Hq, w.D), device="cuda")
+        o_p = torch.randn_like(o_a)
+        l_a = torch.randn((w.B, w.Hq, w.Sq), device="cuda")
+        l_p = torch.randn_like(l_a)
+        sets.append((o_a, l_a, o_p, l_p))
+    for i in range(4):
+        st.st_attn_merge(*sets[i])
+    n = 16
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record()
+    for i in range(n):
+        st.st_attn_merge(*sets[i % 4])
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2]
+    rows = w.B * w.Hq * w.Sq
+    nbytes = rows * (12 * w.D + 12)               # two states read, one written: D + 1 floats each
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
+            "bytes_per_launch": nbytes, "median_ms": round(ms, 4)}
 
 
 def main() -> int:
@@ -143,7 +183,7 @@ def main() -> int:
         achieved = algo[dom] / (step_ms * 1e-3) / 1e12
         peak = PEAK_BF16_TFLOPS if bf16 else 157.3
         roofline = {"kernel": dom, "bound": "mfma" if bf16 else "alu", "achieved": round(achieved, 1), "peak": peak,
-                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": hbm_traffic(dom, w.name),
                     "avg_launch_ms": round(total_ms / max(launches, 1), 4)}
 
     out = {
@@ -159,6 +199,7 @@ def main() -> int:
         "algorithmic_tflop": {"fwd": round(fwd_flop / 1e12, 4), "bwd": round(bwd_flop / 1e12, 4)},
         "roofline": roofline,
         "kernels": per_kernel,
+        "merge_pass": merge_pass(st, torch, w),
         "input_generation_s": round(gen_s, 1),
     }
     if not args.no_cpu_baseline:
