@@ -10,7 +10,9 @@ ragged query tiles) is done afterwards by the general kernel, which folds its ow
 one with the log-sum-exp merge.
 
 MFMA C layout "lane = query column": the exponent reference r (log2 units) and the row sum are one
-register per lane and query block.  The reference is lazy: it only moves, by a whole number of log2 units,
+register per lane and query block.  The Q fragments are multiplied by scale * log2(e) once (and rounded
+to bf16 again), and every S^T accumulator starts from -r instead of zero, so the MFMAs deliver the
+exponent S c - r directly and no VALU instruction is spent on it.  The reference is lazy: it only moves, by a whole number of log2 units,
 when a block's maximum exceeds it by more than GAP, so the rescale factor is an exact power of two and the
 common path never touches the accumulators.
 
@@ -37,7 +39,9 @@ def QF(qb, ks): return 128 + 4 * (8 * qb + ks)
 # ---- VGPRs
 def SBUF(buf, qb): return 32 * buf + 16 * qb        # two score buffers (S, then P in fp32)
 def P16(buf, qb, m): return 64 + 16 * buf + 8 * qb + 4 * m
-def NL(qb): return 96 + qb                          # -r: minus the exponent reference, log2 units
+def NL(qb): return 240 - 16 * qb                     # sixteen copies of -r (minus the exponent reference, log2 units):
+                                                     # the C operand that starts every S^T accumulator
+                                                     # (NL(1) reuses the input registers once the prologue has read them)
 def LSUM(qb, m): return 98 + 2 * qb + m             # partial row sums (this lane's key rows)
 def MX(qb): return 102 + qb                         # block maximum, then d = max * c - r
 ONES, GAPR, DMAX = 104, 105, 106                     # packed bf16 (1, 1); GAP; max over both query blocks of d
@@ -118,7 +122,7 @@ def read_vt(p, blk, m, db, seq):
 
 
 def valu_max(buf):
-    """Row maximum of S in buffer `buf`, both halves of the wavefront, and d = max * c - r per query block."""
+    """d = row maximum of the exponents S c - r in buffer `buf`, both halves of the wavefront, per query block."""
     out = []
     for qb in range(QB):
         s0 = SBUF(buf, qb)
@@ -135,23 +139,18 @@ def valu_max(buf):
     out.append("s_nop 1")
     for qb in range(QB):
         out.append(f"v_max_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(TMP + qb)}")
-    for qb in range(QB):
-        out.append(f"v_fma_f32 {vr(MX(qb))}, {vr(MX(qb))}, {sr(S_CEXP)}, {vr(NL(qb))}")
     out.append(f"v_max_f32 {vr(DMAX)}, {vr(MX(0))}, {vr(MX(1))}")
     return out
 
 
 def valu_exp(sbuf, pbuf):
-    """P = exp2(S c - r) in place, packed to bf16 into P buffer `pbuf`, row sums of the packed values."""
+    """P = exp2(exponent) in place, packed to bf16 into P buffer `pbuf`, row sums of the packed values."""
     out = []
     for qb in range(QB):
         for m in range(2):
             rs = [SBUF(sbuf, qb) + 8 * m + i for i in range(8)]
-            for half in range(2):
-                for r in rs[4 * half:4 * half + 4]:
-                    out.append((f"v_fma_f32 {vr(r)}, {vr(r)}, {sr(S_CEXP)}, {vr(NL(qb))}", (), 1))
-                for r in rs[4 * half:4 * half + 4]:
-                    out.append((f"v_exp_f32 {vr(r)}, {vr(r)}", (), 2))
+            for r in rs:
+                out.append((f"v_exp_f32 {vr(r)}, {vr(r)}", (), 2))
             for i in range(4):
                 d = P16(pbuf, qb, m) + i
                 out.append((f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(rs[2 * i])}, {vr(rs[2 * i + 1])}", (d,), 1))
@@ -209,7 +208,7 @@ def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, pr
             tag = f"k{seq}_{ks}"
             e.need(tag)
             d = vr(SBUF(par, qb), 16)
-            e.mfma(d, vr(p.use(tag), 4), ar(QF(qb, ks), 4), "0" if ks == 0 else d)
+            e.mfma(d, vr(p.use(tag), 4), ar(QF(qb, ks), 4), vr(NL(qb), 16) if ks == 0 else d)
         units = 0
         for fn in reads[k]:
             n0 = len(e.ds)
@@ -242,8 +241,9 @@ def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, pr
 def gen_rescale_routine(e, pbuf):
     """Called when some row's block maximum exceeds its reference by more than GAP.  MFMA slots 0..BRANCH_SLOT of
     the calling block have been issued (all of m = 0 and db = 0 of m = 1); the rest of m = 1 still reads P buffer
-    `pbuf`.  Moves the reference of the jumping rows up by k = ceil(d) log2 units: accumulators, row sums and
-    the pending packed P values are multiplied by 2^-k (exact)."""
+    `pbuf`; the exponents in score buffer 1 - pbuf wait for their softmax.  Moves the reference of the jumping rows
+    up by k = ceil(d) log2 units: accumulators, row sums and the pending packed P values are multiplied by 2^-k
+    (exact), k is taken off the waiting exponents and off the start values of the S^T accumulators."""
     e.raw("s_nop 7")
     e.raw("s_nop 7")
     e.raw("s_nop 7")
@@ -254,7 +254,10 @@ def gen_rescale_routine(e, pbuf):
         e.raw(f"v_cmp_gt_f32 vcc, {vr(MX(qb))}, {vr(GAPR)}")
         e.raw("s_nop 1")
         e.raw(f"v_cndmask_b32 {vr(k)}, 0, {vr(k)}, vcc")
-        e.raw(f"v_sub_f32 {vr(NL(qb))}, {vr(NL(qb))}, {vr(k)}")
+        for v in range(16):
+            e.raw(f"v_sub_f32 {vr(NL(qb) + v)}, {vr(NL(qb) + v)}, {vr(k)}")
+        for v in range(16):             # exponents of the block whose softmax comes next: they carry the old reference
+            e.raw(f"v_sub_f32 {vr(SBUF(1 - pbuf, qb) + v)}, {vr(SBUF(1 - pbuf, qb) + v)}, {vr(k)}")
         e.raw(f"v_cvt_i32_f32 {vr(ki)}, {vr(k)}")
         e.raw(f"v_sub_u32 {vr(ki)}, 0, {vr(ki)}")
         e.raw(f"v_ldexp_f32 {vr(alpha[qb])}, 1.0, {vr(ki)}")
@@ -371,12 +374,22 @@ def generate():
         for m in range(2):
             e.raw(f"v_mov_b32 {vr(LSUM(qb, m))}, 0")
     e.raw("s_waitcnt vmcnt(0)")
+    e.comment("Q <- bf16(Q * scale * log2(e)): the MFMAs then deliver exponents in log2 units")
+    for i in range(0, 64, 4):
+        for j in range(4):
+            e.raw(f"v_lshlrev_b32 {vr(64 + 2 * j)}, 16, {vr(i + j)}")
+            e.raw(f"v_and_b32 {vr(65 + 2 * j)}, 0xffff0000, {vr(i + j)}")
+        for j in range(8):
+            e.raw(f"v_mul_f32 {vr(64 + j)}, {sr(S_CEXP)}, {vr(64 + j)}")
+        for j in range(4):
+            e.raw(f"v_cvt_pk_bf16_f32 {vr(i + j)}, {vr(64 + 2 * j)}, {vr(65 + 2 * j)}")
     for i in range(64):
         e.raw(f"v_accvgpr_write_b32 {ar(128 + i)}, {vr(i)}")
     e.raw("s_barrier")
 
-    e.comment("---- pipeline fill: S^T of blocks (0,0) and (0,1); reference, P and row sums of block (0,0)")
-    for blk, buf, seq in (((0, 0), 0, -2), ((0, 1), 1, -1)):
+    e.comment("---- pipeline fill: exponents of block (0,0) from zero, reference, P and row sums; then block (0,1) from -r")
+
+    def fill_s(blk, buf, seq, c_init):
         for ks in range(KS):
             read_k(p, blk, ks, seq)
             if ks % 4 == 3:
@@ -384,16 +397,20 @@ def generate():
                     e.need(f"k{seq}_{k2}")
                     for qb in range(QB):
                         d = vr(SBUF(buf, qb), 16)
-                        e.mfma(d, vr(p.use(f"k{seq}_{k2}"), 4), ar(QF(qb, k2), 4), "0" if k2 == 0 else d)
+                        e.mfma(d, vr(p.use(f"k{seq}_{k2}"), 4), ar(QF(qb, k2), 4), c_init(qb) if k2 == 0 else d)
+
+    fill_s((0, 0), 0, -2, lambda qb: "0")
     e.raw("s_nop 7")
     e.raw("s_nop 7")
-    e.raw(f"v_mov_b32 {vr(NL(0))}, 0")
-    e.raw(f"v_mov_b32 {vr(NL(1))}, 0")
-    for ln in valu_max(0):                      # with r = 0: d = max * c
+    for ln in valu_max(0):                      # with r = 0: d = row maximum of S c
         e.raw(ln)
-    for qb in range(QB):                        # reference = ceil(max * c), whole log2 units
+    for qb in range(QB):                        # reference = ceil(max), whole log2 units; shift block (0,0) by hand
         e.raw(f"v_ceil_f32 {vr(MX(qb))}, {vr(MX(qb))}")
-        e.raw(f"v_sub_f32 {vr(NL(qb))}, 0, {vr(MX(qb))}")
+        for v in range(16):
+            e.raw(f"v_sub_f32 {vr(NL(qb) + v)}, 0, {vr(MX(qb))}")
+        for v in range(16):
+            e.raw(f"v_sub_f32 {vr(SBUF(0, qb) + v)}, {vr(SBUF(0, qb) + v)}, {vr(MX(qb))}")
+    fill_s((0, 1), 1, -1, lambda qb: vr(NL(qb), 16))
     for text, writes, _ in valu_exp(0, 0):
         e.valu(text, writes)
     for db in range(2):
