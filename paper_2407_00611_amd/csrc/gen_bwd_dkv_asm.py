@@ -12,9 +12,10 @@ resident K fragments and the score tiles in VGPRs) and a fixed interleave of MFM
 Work of one workgroup (4 wavefronts): 256 keys of one KV head of one chunk (64 per wavefront), against a
 run of 32-query blocks that see every one of those keys (no masking in here; blocks that need a mask go
 to the general kernel).  Per block and wavefront, with the MFMA C layout "lane = key column":
-    phase 1   S   = Q K^T                       A: Q rows from LDS,        B: resident K fragments
+    phase 1   E   = Q K'^T - lse log2e          A: Q rows from LDS,        B: resident K fragments, pre-multiplied
+                                                by scale * log2(e) (and rounded to bf16 again), C init: -lse log2e
     phase 2   dP' = dO V^T - Delta              A: dO rows from LDS,       B: V rows from LDS, C init: -Delta
-              VALU: P = exp2(S c - lse log2e), bf16 pack              (runs under phase 2 / 3 MFMAs)
+              VALU: P = exp2(E), bf16 pack                            (runs under phase 2 / 3 MFMAs)
     phase 3   dV^T += dO^T P                    A: dO^T by LDS transpose reads, B: packed P
               VALU: dS = P dP', bf16 pack (in place)                   (runs under phase 3 / 4 MFMAs)
     phase 4   dK^T += Q^T dS                    A: Q^T by LDS transpose reads,  B: packed dS
@@ -187,8 +188,8 @@ def plan_reads(e, pool, u, seq):
     for ks in range(KS):
         plan(2 * ks, rd_nat(f"{seq}q{ks}", qt, ks, X, NKB))
         if ks == 0:
-            plan(0, rd_stat(f"{seq}nd", ND, stats + 128))
-            plan(1, rd_stat(f"{seq}nl", NL, stats))
+            plan(0, rd_stat(f"{seq}nl", NL, stats))
+            plan(1, rd_stat(f"{seq}nd", ND, stats + 128))
     for ks in range(KS):
         base = 16 + 2 * ks
         plan(base, rd_nat(f"{seq}do{ks}", dot_, ks, X, NKB))
@@ -226,14 +227,12 @@ def gen_step(e, pool, u, seq, reads, next_reads):
     valu = []
     def S(nb, v): return S0 + 16 * nb + v
     def DP(nb, v): return DP0 + 16 * nb + v
-    # VALU-1: P = exp2(S c + nl); pack P.  S[nb] is written by slot 14 + nb; its first reader comes three MFMA issues later.
+    # VALU-1: P = exp2(E); pack P.  S[nb] is written by slot 14 + nb; its first reader comes three MFMA issues later.
     for m in range(2):
         for nb in range(NKB):
             early = 17 + nb
             for grp in range(2):
                 vs = [8 * m + 4 * grp + i for i in range(4)]
-                for v in vs:
-                    valu.append((early, f"v_fma_f32 {vr(S(nb, v))}, {vr(S(nb, v))}, {sr(S_CEXP)}, {vr(NL + v)}", (), 1, f"{seq}nl{v // 4}"))
                 for v in vs:
                     valu.append((early, f"v_exp_f32 {vr(S(nb, v))}, {vr(S(nb, v))}", (), 2, None))
                 if grp == 1:
@@ -258,7 +257,7 @@ def gen_step(e, pool, u, seq, reads, next_reads):
     def emit_valu(item):
         _, text, writes, units, needtag = item
         if needtag:
-            assert cur_slot[0] < 65 - LAT, "statistics registers are reloaded for the next block at the tail"
+            assert False, "no VALU instruction reads the statistics any more"
             e.need(needtag)
         e.valu(text, writes)
         for r in writes:
@@ -290,7 +289,11 @@ def gen_step(e, pool, u, seq, reads, next_reads):
             _, ks, nb = sl
             tag = f"{seq}q{ks}"
             e.need(tag)
-            c = "0" if ks == 0 else vr(S0 + 16 * nb, 16)
+            if ks == 0:
+                e.need(f"{seq}nl3")
+                c = vr(NL, 16)
+            else:
+                c = vr(S0 + 16 * nb, 16)
             e.mfma(vr(S0 + 16 * nb, 16), vr(pool.use(tag), 4), vr(KF(nb, ks), 4), c)
         elif ph == "dP":
             _, ks, nb = sl
@@ -407,6 +410,15 @@ def generate():
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
     e.comment("statistics of block 0 to LDS stage 0, then block 2 requested (its statistics reuse block 0's registers)")
     e.raw("s_waitcnt vmcnt(6)")
+    e.comment("K <- bf16(K * scale * log2(e)): the phase-1 MFMAs then deliver exponents in log2 units")
+    for i in range(0, 64, 4):
+        for j in range(4):
+            e.raw(f"v_lshlrev_b32 {vr(S0 + 2 * j)}, 16, {vr(i + j)}")
+            e.raw(f"v_and_b32 {vr(S0 + 1 + 2 * j)}, 0xffff0000, {vr(i + j)}")
+        for j in range(8):
+            e.raw(f"v_mul_f32 {vr(S0 + j)}, {sr(S_CEXP)}, {vr(S0 + j)}")
+        for j in range(4):
+            e.raw(f"v_cvt_pk_bf16_f32 {vr(i + j)}, {vr(S0 + 2 * j)}, {vr(S0 + 1 + 2 * j)}")
     stat_publish(e, 0, 0, "stw")
     e.raw("s_waitcnt lgkmcnt(0)")
     e.ds = []

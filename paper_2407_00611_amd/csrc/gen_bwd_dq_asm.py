@@ -8,6 +8,9 @@ of one head, 64 per wavefront as two 32-query blocks, and walks the 64-key tiles
 rows sees in full (tiles that need a mask, ragged tails and ragged query tiles go to the general kernel).
 The MFMA C layout is "lane = query column", so lse and Delta are one register per lane and block.
 Q and dO fragments stay in AGPRs (MFMA B operands may come from there), the dQ^T accumulators too.
+The Q fragments are multiplied by scale * log2(e) once (and rounded to bf16 again) and the S^T accumulators
+start from -lse * log2(e), the dP'^T accumulators from -Delta: the MFMAs deliver the exponent of P and
+dP - Delta directly.
 
 Per 32-key block i and wavefront, three groups of 16 MFMAs, software-pipelined across blocks so that
 every VALU result is needed one group later than it is produced:
@@ -33,18 +36,19 @@ def DOF(qb, ks): return 192 + 4 * (8 * qb + ks)
 def SBUF(buf, qb): return 32 * buf + 16 * qb        # two score buffers (later P, fp32)
 def DP(qb): return 64 + 16 * qb                     # dP', later dS, later packed dS in [4m .. 4m+3]
 def ND(qb): return 96 + 16 * qb                     # sixteen copies of -Delta (MFMA C operand)
-def NL(qb): return 128 + qb                         # -lse * log2(e)
-POOL0 = 132                                          # 3 rings x 4 fragments x 4 registers
-TMP = 180                                            # 180..187
-XL, XH = 188, 196                                    # natural-read offsets: stages 0-1 / stages 2-3
-TRLO_L, TRHI_L, TRLO_H, TRHI_H = 204, 208, 212, 216
-KOFF, VOFF = 244, 248                                # per-lane global offsets of the 4 DMA instructions per tensor
-DQOFF = 252
-# inputs (pinned by the C++ side)
-IN_VA, IN_VB = 224, 240                              # v[224:239], v[240:243]
-I_QROW0, I_QROW1, I_DOROW0, I_DOROW1 = 224, 226, 228, 230
-I_NL0, I_NL1, I_ND0, I_ND1, I_XBASE, I_GF16, I_TRBASE, I_LF16 = 232, 233, 234, 235, 236, 237, 238, 239
-I_KOFF0, I_VOFF0, I_DQOFF = 240, 241, 242
+def NL(qb): return 128 + 16 * qb                    # sixteen copies of -lse * log2(e) (MFMA C operand)
+POOL0 = 160                                          # 3 rings x 4 fragments x 4 registers
+TMP = 208                                            # 208..214
+DQOFF = 215
+XL, XH = 216, 224                                    # natural-read offsets: stages 0-1 / stages 2-3
+TRLO_L, TRHI_L, TRLO_H, TRHI_H = 232, 236, 240, 244
+KOFF, VOFF = 248, 252                                # per-lane global offsets of the 4 DMA instructions per tensor
+# inputs (pinned by the C++ side) sit in the fragment pool, which the prologue does not use
+IN_VA, IN_VB = 160, 176                              # v[160:175], v[176:179]
+I_QROW0, I_QROW1, I_DOROW0, I_DOROW1 = 160, 162, 164, 166
+I_NL0, I_NL1, I_ND0, I_ND1, I_XBASE, I_GF16, I_TRBASE, I_LF16 = 168, 169, 170, 171, 172, 173, 174, 175
+I_KOFF0, I_VOFF0, I_DQOFF = 176, 177, 178
+PT = 184                                             # 184..199: temporaries of the prologue
 (S_LDS, S_WAVE, S_NT, S_KRS16, S_VRS16, S_SCALE, S_DQPTR, S_DQQB, S_TBL, S_KTILE, S_VTILE) = (32, 33, 34, 35, 36, 37, 38, 40, 41, 42, 43)
 # scalar temporaries
 S_CEXP, T_M0, T_REM, D_KPTR, D_VPTR, D_LEFT, D_IDX, D_TBL, T_X = 47, 64, 65, 66, 68, 70, 71, 72, 73
@@ -166,12 +170,10 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
                     valu.append((2 + qb, f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1))
     # the first VALU reader of an MFMA result comes three MFMA issues after the MFMA
     early1 = 17 if do_b else 34
-    if do_ac:  # P(i+1) = exp2(S c + nl); S^T(i+1)[qb] is written by slot 14 + qb
+    if do_ac:  # P(i+1) = exp2(exponent); S^T(i+1)[qb] is written by slot 14 + qb
         for qb in range(QB):
             for grp in range(4):
                 vs = [SBUF(nbuf, qb) + 4 * grp + i for i in range(4)]
-                for r in vs:
-                    valu.append((early1 + qb, f"v_fma_f32 {vr(r)}, {vr(r)}, {sr(S_CEXP)}, {vr(NL(qb))}", (), 1))
                 for r in vs:
                     valu.append((early1 + qb, f"v_exp_f32 {vr(r)}, {vr(r)}", (), 2))
     vi = [0]
@@ -197,7 +199,7 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
             tag = f"k{seq}_{ks}"
             e.need(tag)
             d = vr(SBUF(nbuf, qb), 16)
-            e.mfma(d, vr(p.use(tag), 4), ar(QF(qb, ks), 4), "0" if ks == 0 else d)
+            e.mfma(d, vr(p.use(tag), 4), ar(QF(qb, ks), 4), vr(NL(qb), 16) if ks == 0 else d)
         elif sl[0] == "B":
             _, m, db, qb = sl
             tag = f"t{seq}_{m}_{db}"
@@ -311,14 +313,24 @@ def generate():
     for i in range(128):
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
     e.raw("s_waitcnt vmcnt(0)")
+    e.comment("Q <- bf16(Q * scale * log2(e)): the S^T MFMAs then deliver exponents in log2 units")
+    for i in range(0, 64, 4):
+        for j in range(4):
+            e.raw(f"v_lshlrev_b32 {vr(PT + 2 * j)}, 16, {vr(i + j)}")
+            e.raw(f"v_and_b32 {vr(PT + 1 + 2 * j)}, 0xffff0000, {vr(i + j)}")
+        for j in range(8):
+            e.raw(f"v_mul_f32 {vr(PT + j)}, {sr(S_CEXP)}, {vr(PT + j)}")
+        for j in range(4):
+            e.raw(f"v_cvt_pk_bf16_f32 {vr(i + j)}, {vr(PT + 2 * j)}, {vr(PT + 1 + 2 * j)}")
     for i in range(64):
         e.raw(f"v_accvgpr_write_b32 {ar(128 + i)}, {vr(i)}")
         e.raw(f"v_accvgpr_write_b32 {ar(192 + i)}, {vr(64 + i)}")
-    e.raw(f"v_mov_b32 {vr(NL(0))}, {vr(I_NL0)}")
-    e.raw(f"v_mov_b32 {vr(NL(1))}, {vr(I_NL1)}")
     for qb, src in ((0, I_ND0), (1, I_ND1)):
         for v in range(16):
             e.raw(f"v_mov_b32 {vr(ND(qb) + v)}, {vr(src)}")
+    for qb, src in ((0, I_NL0), (1, I_NL1)):
+        for v in range(16):
+            e.raw(f"v_mov_b32 {vr(NL(qb) + v)}, {vr(src)}")
     e.raw("s_barrier")
     e.comment("pipeline fill: S^T, P and dP' of block (0, 0)")
     gen_block(p, None, (0, 0), (0, 1), 1, 0, do_b=False, prefetched=False)
@@ -385,7 +397,7 @@ def generate():
 
 def main():
     e = generate()
-    clob = [f"v{i}" for i in range(256) if not 224 <= i < 244] + [f"a{i}" for i in range(256)]
+    clob = [f"v{i}" for i in range(256) if not 160 <= i < 180] + [f"a{i}" for i in range(256)]
     clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 76)]
     write_inc(sys.stdout, "gen_bwd_dq_asm.py", "ST_DQ_FAST", e, LDS_BYTES, clob)
 
