@@ -22,43 +22,61 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 // straddles a wavefront: every lane of the row has read lse_acc before lane 0 overwrites it.
 // Weights: w_acc = exp(lse_acc - lse'), w_part = exp(lse_part - lse'), lse' = max + log(sum).
 // A side with lse = -inf gets weight 0 without ever forming (-inf) - (-inf).
+constexpr int kMergeUnroll = 4;   // vectors per thread: all loads of a thread are in flight before its first store
+
 template <bool kLowp>
 __global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, float* __restrict__ lse_acc,
                                                     const float* __restrict__ o_part,
                                                     const float* __restrict__ lse_part, int64_t n_rows,
                                                     int32_t Sq, int32_t Hq, int32_t vec_per_row,
                                                     int32_t lane_shift, uint2* __restrict__ o_lowp) {
-  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = tid >> lane_shift;             // (b * Sq + i) * Hq + h
-  const int32_t sub = (int32_t)(tid & ((1 << lane_shift) - 1));
-  if (row >= n_rows || sub >= vec_per_row) return;
-  const int64_t v = row * vec_per_row + sub;
-  const int32_t h = (int32_t)(row % Hq);
-  const int64_t bi = row / Hq;
-  const int32_t i = (int32_t)(bi % Sq);
-  const int64_t b = bi / Sq;
-  const int64_t sidx = (b * Hq + h) * Sq + i;
-  const float la = lse_acc[sidx], lp = lse_part[sidx];
-  const float m = fmaxf(la, lp);
-  float wa = 0.f, wp = 0.f, lnew = -INFINITY;
-  if (m != -INFINITY) {
-    const float ea = expf(la - m), ep = expf(lp - m);  // exp(-inf) = 0 for an empty side
-    const float sum = ea + ep;
-    lnew = m + logf(sum);
-    const float inv = 1.f / sum;
-    wa = ea * inv;
-    wp = ep * inv;
+  int64_t v[kMergeUnroll], sidx[kMergeUnroll];
+  bool live[kMergeUnroll], first[kMergeUnroll];
+  float la[kMergeUnroll], lp[kMergeUnroll];
+  float4 a[kMergeUnroll], p[kMergeUnroll];
+#pragma unroll
+  for (int u = 0; u < kMergeUnroll; ++u) {
+    const int64_t tid = ((int64_t)blockIdx.x * kMergeUnroll + u) * 256 + threadIdx.x;
+    const int64_t row = tid >> lane_shift;             // (b * Sq + i) * Hq + h
+    const int32_t sub = (int32_t)(tid & ((1 << lane_shift) - 1));
+    live[u] = row < n_rows && sub < vec_per_row;
+    first[u] = sub == 0;
+    const int64_t rr = live[u] ? row : 0;
+    v[u] = rr * vec_per_row + (live[u] ? sub : 0);
+    const int32_t h = (int32_t)(rr % Hq);
+    const int64_t bi = rr / Hq;
+    sidx[u] = ((bi / Sq) * Hq + h) * Sq + (bi % Sq);
+    la[u] = lse_acc[sidx[u]];
+    lp[u] = lse_part[sidx[u]];
+    a[u] = reinterpret_cast<const float4*>(o_acc)[v[u]];
+    {
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(o_part) + v[u]);   // read once
+      p[u] = make_float4(t.x, t.y, t.z, t.w);
+    }
   }
-  const float4 a = reinterpret_cast<const float4*>(o_acc)[v];
-  const float4 p = reinterpret_cast<const float4*>(o_part)[v];
-  float4 r;
-  r.x = wa * a.x + wp * p.x;
-  r.y = wa * a.y + wp * p.y;
-  r.z = wa * a.z + wp * p.z;
-  r.w = wa * a.w + wp * p.w;
-  reinterpret_cast<float4*>(o_acc)[v] = r;
-  if (kLowp) o_lowp[v] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
-  if (sub == 0) lse_acc[sidx] = lnew;
+#pragma unroll
+  for (int u = 0; u < kMergeUnroll; ++u) {
+    if (!live[u]) continue;
+    const float m = fmaxf(la[u], lp[u]);
+    float wa = 0.f, wp = 0.f, lnew = -INFINITY;
+    if (m != -INFINITY) {
+      const float ea = expf(la[u] - m), ep = expf(lp[u] - m);  // exp(-inf) = 0 for an empty side
+      const float sum = ea + ep;
+      lnew = m + logf(sum);
+      const float inv = 1.f / sum;
+      wa = ea * inv;
+      wp = ep * inv;
+    }
+    float4 r;
+    r.x = wa * a[u].x + wp * p[u].x;
+    r.y = wa * a[u].y + wp * p[u].y;
+    r.z = wa * a[u].z + wp * p[u].z;
+    r.w = wa * a[u].w + wp * p[u].w;
+    reinterpret_cast<float4*>(o_acc)[v[u]] = r;
+    if (kLowp) o_lowp[v[u]] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
+    if (first[u]) lse_acc[sidx[u]] = lnew;
+  }
 }
 
 // fp32 "lowp" copy for the fp32 storage dtype
@@ -146,7 +164,7 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
   if (n_vec == 0) return hipSuccess;
   int lane_shift = 0;
   while ((1 << lane_shift) < D / 4) ++lane_shift;      // D <= 256 -> at most 64 lanes per row
-  const unsigned blocks = blocks_for(n_rows << lane_shift);
+  const unsigned blocks = blocks_for(((n_rows << lane_shift) + kMergeUnroll - 1) / kMergeUnroll);
   ProfScope prof("merge", s);
   if (o_lowp != nullptr && lowp_dtype == ST_BF16) {
     hipLaunchKernelGGL(merge_kernel<true>, dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part,
