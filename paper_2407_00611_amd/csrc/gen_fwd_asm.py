@@ -121,8 +121,10 @@ def read_vt(p, blk, m, db, seq):
     p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(hi + db)} offset:{off}", tag)
 
 
-def valu_max(buf):
-    """d = row maximum of the exponents S c - r in buffer `buf`, both halves of the wavefront, per query block."""
+def valu_max(buf, full=False):
+    """d = maximum of the exponents S c - r in buffer `buf` over this lane's key rows (full: over both halves of the
+    wavefront, i.e. the whole block), per query block.  The test against GAP is a wavefront-wide vote, so the
+    common path does not need the halves combined."""
     out = []
     for qb in range(QB):
         s0 = SBUF(buf, qb)
@@ -130,7 +132,15 @@ def valu_max(buf):
         for v in range(3, 15, 2):
             out.append(f"v_max3_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(s0 + v)}, {vr(s0 + v + 1)}")
         out.append(f"v_max_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(s0 + 15)}")
-    # the two halves hold different key rows of the same query column: exchange and combine
+    if full:
+        out += valu_exchange()
+    out.append(f"v_max_f32 {vr(DMAX)}, {vr(MX(0))}, {vr(MX(1))}")
+    return out
+
+
+def valu_exchange():
+    """The two halves of the wavefront hold different key rows of the same query column: make MX the maximum of both."""
+    out = []
     for qb in range(QB):
         out.append(f"v_mov_b32 {vr(TMP + qb)}, {vr(MX(qb))}")
     out.append("s_nop 1")
@@ -139,7 +149,6 @@ def valu_max(buf):
     out.append("s_nop 1")
     for qb in range(QB):
         out.append(f"v_max_f32 {vr(MX(qb))}, {vr(MX(qb))}, {vr(TMP + qb)}")
-    out.append(f"v_max_f32 {vr(DMAX)}, {vr(MX(0))}, {vr(MX(1))}")
     return out
 
 
@@ -247,6 +256,8 @@ def gen_rescale_routine(e, pbuf):
     e.raw("s_nop 7")
     e.raw("s_nop 7")
     e.raw("s_nop 7")
+    for ln in valu_exchange():          # both halves of a query column must move their reference by the same amount
+        e.raw(ln)
     alpha = [RT, RT + 1]
     for qb in range(QB):
         k, ki = RT + 2 + qb, RT + 4 + qb
@@ -402,7 +413,7 @@ def generate():
     fill_s((0, 0), 0, -2, lambda qb: "0")
     e.raw("s_nop 7")
     e.raw("s_nop 7")
-    for ln in valu_max(0):                      # with r = 0: d = row maximum of S c
+    for ln in valu_max(0, full=True):           # with r = 0: d = row maximum of S c
         e.raw(ln)
     for qb in range(QB):                        # reference = ceil(max), whole log2 units; shift block (0,0) by hand
         e.raw(f"v_ceil_f32 {vr(MX(qb))}, {vr(MX(qb))}")
