@@ -117,3 +117,50 @@ def test_backward_is_bit_reproducible():
     # another visit order changes the forward's rounding (hence lse and Delta), so the gradients
     # agree with the oracle (checked inside the helper) but not bit for bit
     _ring_fwd_bwd(w, [3, 1, 0, 2], [0, 1, 0, 1], st.ST_RING_FUSED)
+
+
+BHSD_CASES = [
+    # a chunk table of the maximum length (64 entries) of 64-key chunks: forward and dQ loops
+    si.Workload("fast_bhsd_64chunks", 97, "bf16", 2, 4, 2, 128, 288, 64, 64, 64 * 64 - 288, True, True),
+    # 320-key chunks: the dK/dV loop as well (one full 256-key tile per chunk)
+    si.Workload("fast_bhsd_dkv", 98, "bf16", 2, 4, 2, 128, 288, 320, 3, 3 * 320 - 288, True, True),
+]
+
+
+@pytest.mark.parametrize("w", BHSD_CASES, ids=[w.name for w in BHSD_CASES])
+def test_fast_kernels_strided_layout(w):
+    """[B, heads, S, D] memory behind the same logical views, batch 2, GQA: the hand-scheduled kernels take
+    their strides and chunk pointers from the caller, so the results must be bit-identical to the
+    dense-layout run and match the oracle."""
+    inp = si.make_inputs(w)
+    q, ks, vs, d_o = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    order = list(range(w.n_chunks - 1, -1, -1))
+
+    def bhsd(t):
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)      # same values, [B,H,S,D] memory
+
+    def run(q_, ks_, vs_, do_):
+        o, lse, o_low = st.st_ring_fwd(q_, ks_, vs_, w.q_offset, koffs, w.causal, w.scale, order, None, st.ST_RING_FUSED)
+        dq = torch.zeros_like(o)
+        dk = [torch.zeros(k.shape, device="cuda") for k in ks]
+        dv = [torch.zeros(k.shape, device="cuda") for k in ks]
+        st.st_ring_bwd(q_, ks_, vs_, do_, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv,
+                       st.ST_RING_FUSED)
+        torch.cuda.synchronize()
+        return o, lse, dq, dk, dv
+
+    a = run(q, ks, vs, d_o)
+    b = run(bhsd(q), [bhsd(k) for k in ks], [bhsd(v) for v in vs], bhsd(d_o))
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+    for j in range(w.n_chunks):
+        assert torch.equal(a[3][j], b[3][j]) and torch.equal(a[4][j], b[4][j])
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    dq_r, dk_r, dv_r = oa.attention_backward(inp.q, inp.k, inp.v, inp.d_o, q_pos, k_pos, w.causal, w.scale)
+    assert_close(host(a[0]), o_ref, "bf16", "o")
+    assert_close(host(a[1]), lse_ref, "bf16", "lse", lse=True)
+    assert_close(host(a[2]), dq_r, "bf16", "dq")
+    for j in range(w.n_chunks):
+        assert_close(host(a[3][j]), dk_r[j], "bf16", f"dk[{j}]")
+        assert_close(host(a[4][j]), dv_r[j], "bf16", f"dv[{j}]")
