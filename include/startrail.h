@@ -151,6 +151,34 @@ st_status st_cast_from_f32(const float* src, void* dst, int64_t n, int32_t dst_d
  * Requires C >= 1, C*C | P, 0 <= rank < P (else ST_ERR_INVALID_ARG).  C = 1 is the plain ring. */
 st_status st_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* shard_idx, int32_t* member_of);
 
+/* ---- communication the schedule implies (Section 3.2 "Theoretical Analysis": the three communication
+ * expressions, ring attention's P2P, the concentric layout's collectives and its P2P) ----
+ * For one attention block forward on one GPU: P GPUs, team size C, batch B, sequence N, hidden size H,
+ * bytes_per_element of the exchanged tensors (2 for bf16), link bandwidth W in bytes per second and
+ * per-message latency L in seconds.  Byte counts are exact integers, times are fp64:
+ *   ring_iterations            P - 1                      startrail_iterations            P / C^2 - 1
+ *   ring_p2p_bytes_per_iter    2 B N H e / P              startrail_p2p_bytes_per_iter    2 C B N H e / P
+ *   ring_p2p_bytes             product of the two         startrail_p2p_bytes             product of the two
+ *   startrail_collective_bytes 4 B N H e (C - 1) / P      (team all-gather of Q, K, V + reduce-scatter of O)
+ *   ring_p2p_seconds           iterations * (bytes_per_iter / W + L)        likewise startrail_p2p_seconds
+ *   startrail_collective_seconds   collective_bytes / W   (the paper's expression has no latency term)
+ * Requires C >= 1, C*C | P, P | N, positive sizes, W > 0, L >= 0 (else ST_ERR_INVALID_ARG).  Host-only,
+ * `out` is host memory. */
+typedef struct {
+  int32_t ring_iterations;
+  int32_t startrail_iterations;
+  int64_t ring_p2p_bytes_per_iter;
+  int64_t startrail_p2p_bytes_per_iter;
+  int64_t ring_p2p_bytes;
+  int64_t startrail_p2p_bytes;
+  int64_t startrail_collective_bytes;
+  double ring_p2p_seconds;
+  double startrail_p2p_seconds;
+  double startrail_collective_seconds;
+} st_comm_report;
+st_status st_schedule_report(int32_t P, int32_t C, int64_t B, int64_t N, int64_t H, int32_t bytes_per_element,
+                             double W, double L, st_comm_report* out);
+
 /* ---- driver: the whole share (Algorithm 1 loop + combine; backward loops of Section 3.2) ----
  * order host [n_visit]: chunk indices into the desc tables, in visit order (each at most once).
  * member_of host [n_visit] (nullable = all 0): running state each visit folds into; the member

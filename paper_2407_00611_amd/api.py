@@ -45,6 +45,14 @@ class st_ring_desc(C.Structure):
                 ("k_offset", C.POINTER(C.c_int64))]
 
 
+class st_comm_report(C.Structure):
+    _fields_ = [("ring_iterations", C.c_int32), ("startrail_iterations", C.c_int32),
+                ("ring_p2p_bytes_per_iter", C.c_int64), ("startrail_p2p_bytes_per_iter", C.c_int64),
+                ("ring_p2p_bytes", C.c_int64), ("startrail_p2p_bytes", C.c_int64),
+                ("startrail_collective_bytes", C.c_int64), ("ring_p2p_seconds", C.c_double),
+                ("startrail_p2p_seconds", C.c_double), ("startrail_collective_seconds", C.c_double)]
+
+
 class st_profile_entry(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("total_ms", C.c_float)]
 
@@ -67,6 +75,8 @@ def _load() -> C.CDLL:
         "st_attn_block_bwd": (C.c_int, [D, T, T, T, T, f32p, f32p, f32p, f32p, f32p, vp]),
         "st_cast_from_f32": (C.c_int, [f32p, vp, C.c_int64, C.c_int32, vp]),
         "st_visit_order": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, i32p, i32p]),
+        "st_schedule_report": (C.c_int, [C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
+                                         C.c_double, C.c_double, C.POINTER(st_comm_report)]),
         "st_ring_workspace_bytes": (C.c_size_t, [R, C.c_int32, C.c_int32]),
         "st_ring_fwd": (C.c_int, [R, T, i32p, i32p, C.c_int32, C.c_int32, f32p, f32p, vp, vp, C.c_size_t, vp]),
         "st_ring_bwd": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
@@ -85,7 +95,7 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_delta", "st_attn_block_bwd", "st_cast_from_f32",
-           "st_visit_order", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_profile_begin",
+           "st_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_profile_begin",
            "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
@@ -219,6 +229,14 @@ def st_cast_from_f32(src, dst_dtype: int, dst=None, stream=None) -> torch.Tensor
         raise ValueError("dst must be contiguous, of dst_dtype and as large as src")
     _check(_lib.st_cast_from_f32(_ptr(src), _ptr(dst), src.numel(), dst_dtype, _stream(stream)), "st_cast_from_f32")
     return dst
+
+
+def st_schedule_report(P: int, Cteam: int, B: int, N: int, H: int, bytes_per_element: int = 2,
+                       W: float = 1.0, L: float = 0.0) -> dict:
+    out = st_comm_report()
+    _check(_lib.st_schedule_report(int(P), int(Cteam), int(B), int(N), int(H), int(bytes_per_element), float(W), float(L),
+                                   C.byref(out)), "st_schedule_report")
+    return {name: getattr(out, name) for name, _ in st_comm_report._fields_}
 
 
 def st_visit_order(P: int, Cteam: int, rank: int) -> Tuple[List[int], List[int]]:

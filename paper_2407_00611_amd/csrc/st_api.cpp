@@ -341,6 +341,33 @@ st_status st_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* shard_idx,
   return ST_OK;
 }
 
+// Iteration counts and exchanged bytes of plain ring attention and of the concentric layout for one
+// attention block forward on one GPU (Section 3.2, "Theoretical Analysis", its three communication
+// expressions with bandwidth W and latency L).  A ring step hands on one K and one V shard of N/P tokens; a sub-ring step hands on
+// the C shards a team gathered; the team all-gather of Q, K, V and the reduce-scatter of O move
+// (C - 1) / C of 4 tensors of C N / P tokens.
+st_status st_schedule_report(int32_t P, int32_t C, int64_t B, int64_t N, int64_t H, int32_t e, double W, double L,
+                             st_comm_report* out) {
+  if (!out) return fail(ST_ERR_INVALID_ARG, "null output");
+  if (P < 1 || C < 1 || P % C != 0 || (P / C) % C != 0) return fail(ST_ERR_INVALID_ARG, "layout needs C >= 1 and C*C | P (P=%d C=%d)", P, C);
+  if (B < 1 || N < 1 || H < 1 || e < 1 || N % P != 0) return fail(ST_ERR_INVALID_ARG, "sizes must be positive and P must divide N");
+  if (!(W > 0.0) || !(L >= 0.0)) return fail(ST_ERR_INVALID_ARG, "bandwidth must be positive and latency non-negative");
+  const __int128 shard = (__int128)B * (N / P) * H * e;            // bytes of one tensor's shard on one GPU
+  const __int128 limit = ((__int128)1 << 62);
+  if (shard * 4 * P > limit) return fail(ST_ERR_INVALID_ARG, "sizes overflow 64-bit byte counts");
+  out->ring_iterations = P - 1;
+  out->startrail_iterations = P / (C * C) - 1;
+  out->ring_p2p_bytes_per_iter = (int64_t)(2 * shard);
+  out->startrail_p2p_bytes_per_iter = (int64_t)(2 * shard * C);
+  out->ring_p2p_bytes = out->ring_p2p_bytes_per_iter * out->ring_iterations;
+  out->startrail_p2p_bytes = out->startrail_p2p_bytes_per_iter * out->startrail_iterations;
+  out->startrail_collective_bytes = (int64_t)(4 * shard * (C - 1));
+  out->ring_p2p_seconds = out->ring_iterations * ((double)out->ring_p2p_bytes_per_iter / W + L);
+  out->startrail_p2p_seconds = out->startrail_iterations * ((double)out->startrail_p2p_bytes_per_iter / W + L);
+  out->startrail_collective_seconds = (double)out->startrail_collective_bytes / W;
+  return ST_OK;
+}
+
 // Workspace layout (each block 256-byte aligned):
 //   forward, stepwise: partial O, partial lse, member O, member lse
 //   forward, fused:    (only when more than one launch is needed) partial O, partial lse
