@@ -118,6 +118,20 @@ st_status st_attn_merge(float* o_acc, float* lse_acc, const float* o_part, const
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, int32_t out_dtype,
                         void* o_out_lowp, void* hip_stream);
 
+/* ---- ReduceScatter_combine on one GPU (Algorithm 1, last step; Section 3.2 "Forward Propagation": the team
+ * members' intermediate results are amalgamated and each member keeps its own portion of the rows) ----
+ * n_states partial states of the SAME Sq_in query rows, each over a different part of the keys, are
+ * combined in one pass, and only rows [row0, row0 + Sq_out) are kept:
+ *   lse' = log(sum_x exp(lse_x)),   O' = sum_x exp(lse_x - lse') O_x.
+ *   o_parts, lse_parts  host arrays [n_states] of device pointers: fp32 [B,Sq_in,Hq,D] / fp32 [B,Hq,Sq_in]
+ *   o_out fp32 [B,Sq_out,Hq,D], lse_out fp32 [B,Hq,Sq_out] (overwritten; may not alias an input)
+ *   o_out_lowp (nullable): O' rounded to out_dtype, dense [B,Sq_out,Hq,D]
+ * A state with lse = -inf on a row is empty there; a row empty in every state gives O = 0, lse = -inf.
+ * Requires 1 <= n_states <= 64, D <= 256, D % 8 == 0, 0 <= row0, row0 + Sq_out <= Sq_in. */
+st_status st_attn_combine(const float* const* o_parts, const float* const* lse_parts, int32_t n_states,
+                          int32_t B, int32_t Sq_in, int32_t Hq, int32_t D, int32_t row0, int32_t Sq_out,
+                          float* o_out, float* lse_out, int32_t out_dtype, void* o_out_lowp, void* hip_stream);
+
 /* ---- backward preparation (Section 3.2 "Backward Propagation": each iteration mirrors the
  * FlashAttention backward, which needs Delta_i = <dO_i, O_i> of the FINAL merged O) ----
  *   d_o      [B,Sq,Hq,D] in desc->dtype;  o: the final O, in o_dtype (ST_F32 or desc->dtype)
@@ -150,6 +164,17 @@ st_status st_cast_from_f32(const float* src, void* dst, int64_t n, int32_t dst_d
  *   member_of host [P] (out): team member (0..C-1) whose running state the visit folds into
  * Requires C >= 1, C*C | P, 0 <= rank < P (else ST_ERR_INVALID_ARG).  C = 1 is the plain ring. */
 st_status st_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* shard_idx, int32_t* member_of);
+
+/* ---- the literal per-GPU schedule of the concentric layout (Section 3.2: after the team all-gather every
+ * member holds the team's Q, K, V of C N/P tokens; member a of team t then walks its sub-ring of P/C^2
+ * GPUs and meets one gathered team buffer per iteration) ----
+ * For global rank `rank` = t*C + a:
+ *   team_buffer host [P/C^2] (out): index tau of the team whose gathered KV (sequence shards
+ *                                   tau*C .. tau*C+C-1) is met at iteration i = 0 .. P/C^2-1
+ * The rank's partial state covers the C N/P query rows of its team against those buffers; the C members'
+ * partial states combined (st_attn_combine) give the team's attention output.
+ * Requires C >= 1, C*C | P, 0 <= rank < P (else ST_ERR_INVALID_ARG). */
+st_status st_team_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* team_buffer);
 
 /* ---- communication the schedule implies (Section 3.2 "Theoretical Analysis": the three communication
  * expressions, ring attention's P2P, the concentric layout's collectives and its P2P) ----

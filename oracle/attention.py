@@ -180,6 +180,32 @@ def merge(o_a, lse_a, o_b, lse_b):
     return o, lse
 
 
+def combine(o_parts: Sequence, lse_parts: Sequence, row0: int = 0, n_rows: int = None):
+    """``ReduceScatter_combine`` of Algorithm 1 written as its definition: n partial
+    states of the same query rows, each over a different part of the keys, and
+    the run of rows [row0, row0 + n_rows) that is kept:
+        lse' = log(sum_x exp(lse_x)),   O' = sum_x exp(lse_x - lse') O_x
+    An empty state (lse = -inf) contributes nothing; a row empty in every state
+    gives O = 0 and lse = -inf.  o_x: [B,Sq,Hq,D]; lse_x: [B,Hq,Sq]."""
+    o_parts = [_f64(o) for o in o_parts]
+    lse_parts = [_f64(l) for l in lse_parts]
+    Sq = o_parts[0].shape[1]
+    n_rows = Sq - row0 if n_rows is None else n_rows
+    rows = slice(row0, row0 + n_rows)
+    lse_stack = np.stack([l[:, :, rows] for l in lse_parts])              # [n,B,Hq,rows]
+    m = lse_stack.max(axis=0)
+    m_safe = np.where(np.isfinite(m), m, 0.0)
+    with np.errstate(divide="ignore"):
+        lse = m_safe + np.log(np.exp(lse_stack - m_safe).sum(axis=0))
+    lse = np.where(np.isfinite(m), lse, NEG_INF)
+    lse_safe = np.where(np.isfinite(lse), lse, 0.0)
+    o = np.zeros_like(o_parts[0][:, rows])
+    for o_x, l_x in zip(o_parts, lse_stack):
+        w = np.where(np.isfinite(l_x), np.exp(l_x - lse_safe), 0.0)       # [B,Hq,rows]
+        o += w.transpose(0, 2, 1)[..., None] * o_x[:, rows]
+    return o, lse
+
+
 def empty_state(B: int, Sq: int, Hq: int, D: int):
     """Initial running state: O = 0 and lse = -inf (the neutral element of merge)."""
     return np.zeros((B, Sq, Hq, D)), np.full((B, Hq, Sq), NEG_INF)

@@ -106,3 +106,13 @@ def visit_order(P: int, C: int, rank: int) -> Tuple[List[int], List[int]]:
                 shard_idx.append(tau * C + c)
                 member_of.append(a)
     return shard_idx, member_of
+
+
+def team_visit_order(P: int, C: int, rank: int) -> List[int]:
+    """Team buffers GPU ``rank`` computes on, one per sub-ring iteration, read off
+    the cluster simulation (Section 3.2: the literal schedule, in which every GPU
+    holds its team's C N/P queries and meets one gathered team buffer per iteration)."""
+    check_layout(P, C)
+    if not 0 <= rank < P:
+        raise ValueError("rank out of range")
+    return [row[rank] for row in simulate_cluster(P, C)]

@@ -71,10 +71,13 @@ def _load() -> C.CDLL:
     sigs = {
         "st_attn_block_fwd": (C.c_int, [D, T, T, T, f32p, f32p, vp]),
         "st_attn_merge": (C.c_int, [f32p, f32p, f32p, f32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp, vp]),
+        "st_attn_combine": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_int32, C.c_int32, f32p, f32p, C.c_int32, vp, vp]),
         "st_attn_delta": (C.c_int, [D, T, T, C.c_int32, f32p, vp]),
         "st_attn_block_bwd": (C.c_int, [D, T, T, T, T, f32p, f32p, f32p, f32p, f32p, vp]),
         "st_cast_from_f32": (C.c_int, [f32p, vp, C.c_int64, C.c_int32, vp]),
         "st_visit_order": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, i32p, i32p]),
+        "st_team_visit_order": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, i32p]),
         "st_schedule_report": (C.c_int, [C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32,
                                          C.c_double, C.c_double, C.POINTER(st_comm_report)]),
         "st_ring_workspace_bytes": (C.c_size_t, [R, C.c_int32, C.c_int32]),
@@ -94,8 +97,8 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_delta", "st_attn_block_bwd", "st_cast_from_f32",
-           "st_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_profile_begin",
+EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_combine", "st_attn_delta", "st_attn_block_bwd", "st_cast_from_f32",
+           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_profile_begin",
            "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
@@ -196,6 +199,32 @@ def st_attn_merge(o_acc, lse_acc, o_part, lse_part, out_dtype: int = ST_F32, o_o
                               _ptr(o_out_lowp), _stream(stream)), "st_attn_merge")
 
 
+def st_attn_combine(o_parts, lse_parts, row0: int = 0, Sq_out: int = None, out_dtype: int = ST_F32, o_out=None,
+                    lse_out=None, o_out_lowp=None, stream=None):
+    """n partial states of the same rows -> (o_out, lse_out) of rows [row0, row0 + Sq_out)."""
+    n = len(o_parts)
+    if n == 0 or len(lse_parts) != n:
+        raise ValueError("need as many lse_parts as o_parts, at least one")
+    B, Sq_in, Hq, D = o_parts[0].shape
+    Sq_out = Sq_in - row0 if Sq_out is None else Sq_out
+    for x in range(n):
+        _f32_dense(o_parts[x], (B, Sq_in, Hq, D), "o_parts[x]")
+        _f32_dense(lse_parts[x], (B, Hq, Sq_in), "lse_parts[x]")
+    dev = o_parts[0].device
+    o_out = torch.empty((B, Sq_out, Hq, D), dtype=torch.float32, device=dev) if o_out is None else \
+        _f32_dense(o_out, (B, Sq_out, Hq, D), "o_out")
+    lse_out = torch.empty((B, Hq, Sq_out), dtype=torch.float32, device=dev) if lse_out is None else \
+        _f32_dense(lse_out, (B, Hq, Sq_out), "lse_out")
+    if o_out_lowp is not None and (tuple(o_out_lowp.shape) != (B, Sq_out, Hq, D) or not o_out_lowp.is_contiguous()
+                                   or o_out_lowp.dtype != _torch_dtype(out_dtype)):
+        raise ValueError("o_out_lowp must be dense [B,Sq_out,Hq,D] in out_dtype")
+    op = (C.c_void_p * n)(*[_ptr(t) for t in o_parts])
+    lp = (C.c_void_p * n)(*[_ptr(t) for t in lse_parts])
+    _check(_lib.st_attn_combine(op, lp, n, B, Sq_in, Hq, D, int(row0), int(Sq_out), _ptr(o_out), _ptr(lse_out), out_dtype,
+                                _ptr(o_out_lowp), _stream(stream)), "st_attn_combine")
+    return o_out, lse_out
+
+
 def st_attn_delta(d_o, o, delta=None, stream=None) -> torch.Tensor:
     B, Sq, Hq, D = d_o.shape
     delta = torch.empty((B, Hq, Sq), dtype=torch.float32, device=d_o.device) if delta is None else \
@@ -229,6 +258,12 @@ def st_cast_from_f32(src, dst_dtype: int, dst=None, stream=None) -> torch.Tensor
         raise ValueError("dst must be contiguous, of dst_dtype and as large as src")
     _check(_lib.st_cast_from_f32(_ptr(src), _ptr(dst), src.numel(), dst_dtype, _stream(stream)), "st_cast_from_f32")
     return dst
+
+
+def st_team_visit_order(P: int, Cteam: int, rank: int) -> List[int]:
+    out = (C.c_int32 * max(int(P), 1))()              # the library validates the layout; P entries always suffice
+    _check(_lib.st_team_visit_order(int(P), int(Cteam), int(rank), out), "st_team_visit_order")
+    return list(out)[:int(P) // (int(Cteam) * int(Cteam))]
 
 
 def st_schedule_report(P: int, Cteam: int, B: int, N: int, H: int, bytes_per_element: int = 2,

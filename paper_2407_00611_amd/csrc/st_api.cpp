@@ -262,6 +262,36 @@ st_status st_attn_merge(float* o_acc, float* lse_acc, const float* o_part, const
   return ST_OK;
 }
 
+st_status st_attn_combine(const float* const* o_parts, const float* const* lse_parts, int32_t n_states, int32_t B,
+                          int32_t Sq_in, int32_t Hq, int32_t D, int32_t row0, int32_t Sq_out, float* o_out,
+                          float* lse_out, int32_t out_dtype, void* o_out_lowp, void* hip_stream) {
+  if (!o_parts || !lse_parts) return fail(ST_ERR_INVALID_ARG, "null state tables");
+  if (n_states < 1 || n_states > st::kMaxTable) return fail(ST_ERR_INVALID_ARG, "n_states must be 1..%d", st::kMaxTable);
+  if (B < 0 || Sq_in < 0 || Sq_out < 0 || Hq <= 0 || D <= 0) return fail(ST_ERR_INVALID_ARG, "bad sizes");
+  if (row0 < 0 || (int64_t)row0 + Sq_out > Sq_in) return fail(ST_ERR_INVALID_ARG, "rows [%d, %d + %d) are not inside the %d rows of the states", row0, row0, Sq_out, Sq_in);
+  if (D > 256 || D % 8 != 0) return fail(ST_ERR_UNSUPPORTED, "combine needs D <= 256 and D %% 8 == 0");
+  if (out_dtype != ST_F32 && out_dtype != ST_BF16) return fail(ST_ERR_INVALID_ARG, "unknown out_dtype");
+  const int64_t n_in = (int64_t)B * Sq_in * Hq * D, n_out = (int64_t)B * Sq_out * Hq * D;
+  ST_TRY(check_f32("o_out", o_out, n_out));
+  ST_TRY(check_f32("lse_out", lse_out, n_out));
+  if (o_out_lowp && reinterpret_cast<uintptr_t>(o_out_lowp) % 16) return fail(ST_ERR_ALIGNMENT, "o_out_lowp: not 16-byte aligned");
+  st::CombineArgs a;
+  memset(&a, 0, sizeof(a));
+  for (int x = 0; x < n_states; ++x) {
+    ST_TRY(check_f32("o_parts[x]", o_parts[x], n_in));
+    ST_TRY(check_f32("lse_parts[x]", lse_parts[x], n_in));
+    if (n_out > 0 && (o_parts[x] == o_out || lse_parts[x] == lse_out)) return fail(ST_ERR_INVALID_ARG, "an output aliases state %d", x);
+    a.o[x] = o_parts[x];
+    a.lse[x] = lse_parts[x];
+  }
+  if (n_out == 0) return ST_OK;
+  a.n = n_states;
+  a.B = B; a.Sq_in = Sq_in; a.Hq = Hq; a.D = D; a.row0 = row0; a.Sq_out = Sq_out;
+  a.o_out = o_out; a.lse_out = lse_out; a.o_lowp = o_out_lowp;
+  ST_HIP(st::launch_combine(a, out_dtype, (hipStream_t)hip_stream), "st_attn_combine launch");
+  return ST_OK;
+}
+
 st_status st_attn_delta(const st_block_desc* d, const st_tensor* d_o, const st_tensor* o, int32_t o_dtype,
                         float* delta, void* hip_stream) {
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
@@ -338,6 +368,20 @@ st_status st_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* shard_idx,
         member_of[n] = a;
       }
     }
+  return ST_OK;
+}
+
+// Iteration i of GPU (team t, member a) works on the gathered buffer of team ((t - i) mod S) * C + a,
+// S = P / C^2 GPUs per sub-ring (closed form of the initial placement followed by i sub-ring passes).
+st_status st_team_visit_order(int32_t P, int32_t C, int32_t rank, int32_t* team_buffer) {
+  if (!team_buffer) return fail(ST_ERR_INVALID_ARG, "null output");
+  if (P < 1 || C < 1 || P % C != 0 || (P / C) % C != 0) return fail(ST_ERR_INVALID_ARG, "layout needs C >= 1 and C*C | P (P=%d C=%d)", P, C);
+  if (rank < 0 || rank >= P) return fail(ST_ERR_INVALID_ARG, "rank %d outside 0..%d", rank, P - 1);
+  const int32_t S = P / (C * C), t = rank / C, a = rank % C;
+  for (int32_t i = 0; i < S; ++i) {
+    const int32_t pos = ((t - i) % S + S) % S;
+    team_buffer[i] = pos * C + a;
+  }
   return ST_OK;
 }
 

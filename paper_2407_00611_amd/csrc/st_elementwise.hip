@@ -1,4 +1,5 @@
-// HBM-bound passes: log-sum-exp merge of two partial states, Delta = rowsum(dO * O),
+// HBM-bound passes: log-sum-exp merge of two partial states, combine of n partial states,
+// Delta = rowsum(dO * O),
 // fp32 -> storage-dtype casts and the (O = 0, lse = -inf) state fill.
 // One 16-byte vector per lane, rows never straddle a lane; grid sized to the data.
 #include "st_internal.h"
@@ -77,6 +78,65 @@ __global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, f
     if (kLowp) o_lowp[v[u]] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
     if (first[u]) lse_acc[sidx[u]] = lnew;
   }
+}
+
+// ---- combine: n partial states of the same rows -> one state, keeping a run of rows -----------
+// Thread = one float4 of one kept (b, i, h) row, lanes per row as in the merge.  The weights are
+// w_x = exp(lse_x - m) / sum_y exp(lse_y - m) with m the largest lse, so an empty state (lse = -inf)
+// weighs 0 and (-inf) - (-inf) is never formed; a row empty in every state gives O = 0, lse = -inf.
+// The O loads of kCombineUnroll states are in flight together.
+constexpr int kCombineUnroll = 4;
+
+template <bool kLowp>
+__global__ __launch_bounds__(256) void combine_kernel(const CombineArgs a, int32_t vec_per_row, int32_t lane_shift) {
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = tid >> lane_shift;               // (b * Sq_out + i) * Hq + h
+  const int32_t sub = (int32_t)(tid & ((1 << lane_shift) - 1));
+  const int64_t n_rows = (int64_t)a.B * a.Sq_out * a.Hq;
+  if (row >= n_rows || sub >= vec_per_row) return;
+  const int32_t h = (int32_t)(row % a.Hq);
+  const int64_t bi = row / a.Hq;
+  const int64_t b = bi / a.Sq_out;
+  const int32_t i = (int32_t)(bi % a.Sq_out);
+  const int64_t l_in = (b * a.Hq + h) * a.Sq_in + a.row0 + i;
+  const int64_t v_in = ((b * a.Sq_in + a.row0 + i) * a.Hq + h) * vec_per_row + sub;
+
+  float m = -INFINITY;
+  for (int x = 0; x < a.n; ++x) m = fmaxf(m, a.lse[x][l_in]);
+  float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+  float lnew = -INFINITY;
+  if (m != -INFINITY) {
+    float sum = 0.f;
+    for (int x = 0; x < a.n; ++x) sum += expf(a.lse[x][l_in] - m);
+    lnew = m + logf(sum);
+    const float inv = 1.f / sum;
+    for (int x0 = 0; x0 < a.n; x0 += kCombineUnroll) {
+      float4 p[kCombineUnroll];
+      float w[kCombineUnroll];
+#pragma unroll
+      for (int u = 0; u < kCombineUnroll; ++u) {
+        const int x = x0 + u < a.n ? x0 + u : a.n - 1;
+        typedef float f32x4_t __attribute__((ext_vector_type(4)));
+        const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(a.o[x]) + v_in);   // read once
+        p[u] = make_float4(t.x, t.y, t.z, t.w);
+        w[u] = x0 + u < a.n ? expf(a.lse[x][l_in] - m) * inv : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kCombineUnroll; ++u) {
+        // a weight of exactly 0 must not turn a non-finite value of an empty state into NaN
+        if (w[u] != 0.f) {
+          r.x = fmaf(w[u], p[u].x, r.x);
+          r.y = fmaf(w[u], p[u].y, r.y);
+          r.z = fmaf(w[u], p[u].z, r.z);
+          r.w = fmaf(w[u], p[u].w, r.w);
+        }
+      }
+    }
+  }
+  const int64_t v_out = row * vec_per_row + sub;
+  reinterpret_cast<float4*>(a.o_out)[v_out] = r;
+  if (kLowp) reinterpret_cast<uint2*>(a.o_lowp)[v_out] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
+  if (sub == 0) a.lse_out[(b * a.Hq + h) * a.Sq_out + i] = lnew;
 }
 
 // fp32 "lowp" copy for the fp32 storage dtype
@@ -177,6 +237,28 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
   if (e == hipSuccess && o_lowp != nullptr) {
     hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n_vec)), dim3(256), 0, s, (const float4*)o_acc,
                        (float4*)o_lowp, n_vec);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_combine(const CombineArgs& a, int lowp_dtype, hipStream_t s) {
+  const int64_t n_rows = (int64_t)a.B * a.Sq_out * a.Hq;
+  const int64_t n_vec = n_rows * (a.D / 4);
+  if (n_vec == 0) return hipSuccess;
+  int lane_shift = 0;
+  while ((1 << lane_shift) < a.D / 4) ++lane_shift;
+  const unsigned blocks = blocks_for(n_rows << lane_shift);
+  ProfScope prof("combine", s);
+  if (a.o_lowp != nullptr && lowp_dtype == ST_BF16) {
+    hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && a.o_lowp != nullptr) {
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n_vec)), dim3(256), 0, s, (const float4*)a.o_out,
+                       (float4*)a.o_lowp, n_vec);
     e = hipGetLastError();
   }
   return e;

@@ -55,6 +55,18 @@ struct BwdArgs {
   int32_t dq_fast;     // 1: the fast dQ kernel runs too and owns the tiles dq_fast_tiles describes
 };
 
+// n partial states of the same query rows (each O fp32 [B,Sq_in,Hq,D], lse fp32 [B,Hq,Sq_in]) and the run of
+// rows [row0, row0 + Sq_out) the combined state keeps.
+struct CombineArgs {
+  int32_t n;
+  const float* o[kMaxTable];
+  const float* lse[kMaxTable];
+  int32_t B, Sq_in, Hq, D, row0, Sq_out;
+  float* o_out;      // fp32 [B,Sq_out,Hq,D]
+  float* lse_out;    // fp32 [B,Hq,Sq_out]
+  void* o_lowp;      // nullable, [B,Sq_out,Hq,D]
+};
+
 // Split of the dK/dV work between the general kernel and the fast one (head_dim 128): the fast kernel
 // takes, for every FULL tile of kDkvFastKeys keys, the full kDkvFastRows-query blocks from the first one
 // whose rows all see the tile's last key; everything else (masked blocks, ragged tails) stays general.
@@ -111,6 +123,7 @@ hipError_t launch_bwd_dq_fast(const BwdArgs& a, hipStream_t s);
 hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, void* o_lowp, int lowp_dtype,
                         hipStream_t s);
+hipError_t launch_combine(const CombineArgs& a, int lowp_dtype, hipStream_t s);
 hipError_t launch_delta(const View& d_o, int d_o_dtype, const View& o, int o_dtype, float* delta,
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, hipStream_t s);
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hipStream_t s);

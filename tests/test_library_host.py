@@ -36,6 +36,36 @@ def test_visit_order_matches_cluster_simulation(P, C):
         assert st.st_visit_order(P, C, rank) == ov.visit_order(P, C, rank)
 
 
+@pytest.mark.parametrize("P,C", [(1, 1), (4, 1), (4, 2), (8, 2), (16, 2), (16, 4), (32, 2), (32, 4), (64, 2), (64, 4),
+                                 (64, 8), (36, 3), (54, 3)])
+def test_team_visit_order_matches_cluster_simulation(P, C):
+    for rank in range(P):
+        assert st.st_team_visit_order(P, C, rank) == ov.team_visit_order(P, C, rank)
+
+
+def test_team_visit_order_rejects_bad_layouts():
+    for P, C, r in [(8, 3, 0), (8, 4, 0), (0, 1, 0), (8, 0, 0), (12, 4, 0), (8, 2, 8), (8, 2, -1)]:
+        with pytest.raises(st.StarTrailError) as e:
+            st.st_team_visit_order(P, C, r)
+        assert e.value.status == 1
+
+
+def test_combine_validation_fails_before_any_launch():
+    lib = api._lib
+    def call(n=2, B=1, Sq_in=8, Hq=2, D=64, row0=0, Sq_out=8, o=(0x1000, 0x2000), l=(0x3000, 0x4000), out=0x5000,
+             lout=0x6000, dtype=0, low=None):
+        op = (C.c_void_p * len(o))(*o)
+        lp = (C.c_void_p * len(l))(*l)
+        return lib.st_attn_combine(op, lp, n, B, Sq_in, Hq, D, row0, Sq_out, C.c_void_p(out), C.c_void_p(lout), dtype,
+                                   C.c_void_p(low) if low else None, None)
+    assert call(n=0) == 1 and call(n=65) == 1
+    assert call(row0=1) == 1 and call(row0=-1) == 1 and call(Sq_out=9) == 1
+    assert call(D=260) == 2 and call(D=12) == 2
+    assert call(o=(0x1000, 0x2004)) == 3 and call(o=(0x1000, 0)) == 1
+    assert call(out=0x1000) == 1 and call(dtype=7) == 1 and call(low=0x7008, dtype=1) == 3
+    assert call(Sq_out=0, row0=8) == 0 and call(B=0) == 0          # nothing to do: no launch
+
+
 def test_visit_order_rejects_bad_layouts():
     for P, C, r in [(8, 3, 0), (8, 4, 0), (0, 1, 0), (8, 0, 0), (12, 4, 0), (8, 2, 8), (8, 2, -1)]:
         with pytest.raises(st.StarTrailError) as e:

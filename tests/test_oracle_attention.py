@@ -265,6 +265,53 @@ def test_merge_of_two_single_keys_closed_form():
     np.testing.assert_allclose(lse, math.log(math.exp(0.5) + math.exp(-0.25)), atol=1e-15)
 
 
+def test_combine_of_single_keys_closed_form():
+    # three one-key states: lse are the scores, O the value rows -> a 3-way softmax written out
+    scores, values = [0.5, -0.25, 1.5], [3.0, -1.0, 0.25]
+    o_parts = [np.full((1, 1, 1, 2), v) for v in values]
+    l_parts = [np.full((1, 1, 1), s) for s in scores]
+    o, lse = oa.combine(o_parts, l_parts)
+    z = sum(math.exp(s) for s in scores)
+    np.testing.assert_allclose(o, sum(math.exp(s) / z * v for s, v in zip(scores, values)), atol=1e-15)
+    np.testing.assert_allclose(lse, math.log(z), atol=1e-15)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_combine_of_key_subsets_equals_monolithic(causal):
+    """Partial states over disjoint key subsets (what the team members hold), combined in one pass, are the
+    attention over all keys; only the asked rows come back; the order of the states is irrelevant."""
+    q, ks, vs, _, qpos, kpos, _, scale = _case(seed=34, lens=(5, 3, 6, 2, 4), Sq=9, q0=8)
+    o, lse = oa.attention_forward(q, ks, vs, qpos, kpos, causal, scale)
+    groups = [[0, 3], [1], [4, 2]]
+    parts = [oa.attention_forward(q, [ks[j] for j in g], [vs[j] for j in g], qpos, [kpos[j] for j in g], causal, scale)
+             for g in groups]
+    oc, lc = oa.combine([p[0] for p in parts], [p[1] for p in parts])
+    np.testing.assert_allclose(oc, o, atol=1e-13)
+    np.testing.assert_allclose(lc, lse, atol=1e-13)
+    for perm in itertools.permutations(range(3)):
+        op, lp = oa.combine([parts[x][0] for x in perm], [parts[x][1] for x in perm], row0=2, n_rows=5)
+        np.testing.assert_allclose(op, o[:, 2:7], atol=1e-13)
+        np.testing.assert_allclose(lp, lse[:, :, 2:7], atol=1e-13)
+
+
+def test_combine_special_cases():
+    q, ks, vs, _, qpos, kpos, causal, scale = _case(seed=35, q0=2)
+    parts = [oa.block_forward(q, k, v, qpos, p, causal, scale) for k, v, p in zip(ks, vs, kpos)]
+    # one state: identity;  two states: the pairwise merge;  empty states change nothing
+    o1, l1 = oa.combine([parts[0][0]], [parts[0][1]])
+    assert np.array_equal(o1, parts[0][0]) and np.array_equal(l1, parts[0][1])
+    o2, l2 = oa.combine([parts[0][0], parts[1][0]], [parts[0][1], parts[1][1]])
+    om, lm = oa.merge(*parts[0], *parts[1])
+    np.testing.assert_allclose(o2, om, atol=1e-15)
+    np.testing.assert_allclose(l2, lm, atol=1e-15)
+    e = oa.empty_state(*q.shape)
+    o3, l3 = oa.combine([e[0], parts[0][0], e[0], parts[1][0]], [e[1], parts[0][1], e[1], parts[1][1]])
+    np.testing.assert_allclose(o3, om, atol=1e-15)
+    np.testing.assert_allclose(l3, lm, atol=1e-15)
+    o4, l4 = oa.combine([e[0], e[0]], [e[1], e[1]])
+    assert np.array_equal(o4, e[0]) and np.array_equal(l4, e[1]) and not np.isnan(o4).any()
+
+
 @pytest.mark.parametrize("causal", [True, False])
 def test_blockwise_merge_equals_monolithic_for_any_order(causal):
     q, ks, vs, d_o, qpos, kpos, _, scale = _case(seed=32, lens=(5, 3, 6, 2), Sq=8, q0=6)

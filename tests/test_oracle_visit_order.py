@@ -56,6 +56,24 @@ def test_coverage_invariants(P, C):
         assert all(members.count(a) == P // C for a in range(C))
 
 
+def test_team_order_is_the_member_part_of_the_shard_order():
+    """The literal schedule (team buffers met by one GPU) and the one-GPU rendering used for a single shard
+    (all C members in turn, buffers expanded to shards) describe the same walk."""
+    for P, C in [(8, 2), (16, 2), (32, 4), (64, 4), (36, 3), (16, 1)]:
+        S = P // (C * C)
+        for rank in range(P):
+            buffers = ov.team_visit_order(P, C, rank)
+            assert len(buffers) == S and len(set(buffers)) == S
+            assert all(b % C == rank % C for b in buffers)          # member a only meets buffers = a (mod C)
+            shards, members = ov.visit_order(P, C, rank)
+            mine = [s for s, m in zip(shards, members) if m == rank % C]
+            assert mine == [b * C + c for b in buffers for c in range(C)]
+        # the C members of a team meet every team buffer exactly once between them
+        for t0 in range(0, P, C):
+            seen = sorted(b for a in range(C) for b in ov.team_visit_order(P, C, t0 + a))
+            assert seen == list(range(P // C))
+
+
 def test_c1_is_the_plain_ring():
     # Ring attention: rank r starts on its own shard and then receives from its predecessor
     for P, r in [(4, 0), (8, 3), (16, 15)]:
