@@ -8,6 +8,10 @@ A step = one pass of the whole hot path over the workload, with all inputs resid
 The workload is benchmark configuration 4 (GQA 32/8 heads, D=128, Q shard 4096, 32 chunks of
 4096 keys, causal, last rank of a P=32 / C=4 concentric layout) with synthetic N(0,1) bf16 data.
 
+`--shape team` times the same model in the shape one GPU of the concentric layout really sees (the team's
+gathered 16384 queries against the two gathered team buffers this GPU meets, then the 4-way combine that
+keeps its own 4096 rows; backward of the same shape); the default `--shape ring` is the headline workload.
+
 Prints ONE JSON line (see the keys below).  `value` is algorithmic attention TFLOP/s: 4*D per
 visible (query, key) pair forward and 10*D backward, masked pairs and recomputation earn nothing.
 """
@@ -67,6 +71,32 @@ def merge_pass(st, torch, w) -> dict:
             "bytes_per_launch": nbytes, "median_ms": round(ms, 4)}
 
 
+def combine_pass(st, torch, states_o, states_l, n_own, w) -> dict:
+    """HBM rate of the n-way combine (st_attn_combine) as the team-gathered step runs it: C states of the
+    team's rows are read on the kept rows only, one state of n_own rows is written (fp32 and bf16).  The
+    member whose rows are kept rotates, so that a launch finds none of its operands in the last-level cache
+    (C x n_own rows x (4 D + 4) bytes per member, C members)."""
+    Ct = len(states_o)
+    o = torch.empty((w.B, n_own, w.Hq, w.D), dtype=torch.float32, device="cuda")
+    l = torch.empty((w.B, w.Hq, n_own), dtype=torch.float32, device="cuda")
+    low = torch.empty((w.B, n_own, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
+    for a in range(Ct):
+        st.st_attn_combine(states_o, states_l, a * n_own, n_own, st.ST_BF16, o_out=o, lse_out=l, o_out_lowp=low)
+    n = 16
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    ev[0].record()
+    for i in range(n):
+        st.st_attn_combine(states_o, states_l, (i % Ct) * n_own, n_own, st.ST_BF16, o_out=o, lse_out=l, o_out_lowp=low)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2]
+    rows = w.B * w.Hq * n_own
+    nbytes = rows * (Ct * (4 * w.D + 4) + 4 * w.D + 4 + 2 * w.D)
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"kernel": "combine", "states": Ct, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": nbytes, "median_ms": round(ms, 4)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +104,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4)")
     ap.add_argument("--mode", choices=["fused", "stepwise"], default="fused")
+    ap.add_argument("--shape", choices=["ring", "team"], default="ring",
+                    help="ring: a resident N/P-row shard meets every chunk (configurations 1..5); "
+                         "team: the team-gathered shape of the concentric layout (model of configuration 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -90,7 +123,8 @@ def main() -> int:
         print("bench.py needs a GPU (there is no CPU fallback for the HIP path)", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    w = si.paper_workloads()[args.config - 1]
+    team = args.shape == "team"
+    w = si.team_workload() if team else si.paper_workloads()[args.config - 1]
     mode = st.ST_RING_FUSED if args.mode == "fused" else st.ST_RING_STEPWISE
     bf16 = w.dtype == "bf16"
     storage = st.ST_BF16 if bf16 else st.ST_F32
@@ -109,7 +143,9 @@ def main() -> int:
     vs = [up(inp.v_bits[j] if bf16 else None, inp.v[j]) for j in range(w.n_chunks)]
     d_o = up(inp.d_o_bits, inp.d_o) if w.backward else None
     koffs = [w.k_offset(j) for j in range(w.n_chunks)]
-    if w.ring_P:
+    if team:
+        order, members = st.st_team_visit_order(w.ring_P, w.ring_C, w.ring_rank), None
+    elif w.ring_P:
         order, members = st.st_visit_order(w.ring_P, w.ring_C, w.ring_rank)
     else:
         order, members = list(range(w.n_chunks)), None
@@ -132,7 +168,47 @@ def main() -> int:
         dq_low = torch.empty_like(o_low)
         dkv_low = torch.empty(dkv.shape, dtype=q.dtype, device=dev)
 
-    def step():
+    if team:
+        # what the team hands over: the other members' partial states of the same rows (computed here, untimed,
+        # by playing those members), and for the backward the team's final O and lse of all gathered rows
+        Ct, a_r = w.ring_C, w.ring_rank % w.ring_C
+        n_own = w.Sq // Ct
+        others = []
+        for a in range(Ct):
+            if a == a_r:
+                continue
+            ob = st.st_team_visit_order(w.ring_P, w.ring_C, w.ring_rank - a_r + a)
+            o_x, l_x, _ = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, ob, None, mode,
+                                         want_lowp=False, workspace=ws_f)
+            others.append((o_x, l_x))
+        o_own = torch.empty((w.B, n_own, w.Hq, w.D), dtype=torch.float32, device=dev)
+        lse_own = torch.empty((w.B, w.Hq, n_own), dtype=torch.float32, device=dev)
+        o_own_low = torch.empty((w.B, n_own, w.Hq, w.D), dtype=q.dtype, device=dev)
+        st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, mode, o_acc=o_acc, lse=lse,
+                       want_lowp=False, workspace=ws_f)
+        states_o = [o_acc] + [x[0] for x in others]
+        states_l = [lse] + [x[1] for x in others]
+        o_team, lse_team = st.st_attn_combine(states_o, states_l)
+        o_team_low = o_team.to(q.dtype)
+        del o_team
+
+    def step_team():
+        st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, mode,
+                       o_acc=o_acc, lse=lse, want_lowp=False, workspace=ws_f)
+        st.st_attn_combine(states_o, states_l, a_r * n_own, n_own, storage, o_out=o_own, lse_out=lse_own,
+                           o_out_lowp=o_own_low)
+        if w.backward:
+            dq.zero_()
+            for j in order:
+                dkv[:, j].zero_()
+            st.st_ring_bwd(q, ks, vs, d_o, o_team_low, lse_team, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv,
+                           mode, workspace=ws_b)
+            st.st_cast_from_f32(dq, storage, dq_low)
+            for j in order:
+                st.st_cast_from_f32(dkv[0, j], storage, dkv_low[0, j])
+                st.st_cast_from_f32(dkv[1, j], storage, dkv_low[1, j])
+
+    def step_ring():
         st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, mode,
                        o_acc=o_acc, lse=lse, o_lowp=o_low, workspace=ws_f)
         if w.backward:
@@ -142,6 +218,8 @@ def main() -> int:
                            mode, workspace=ws_b)
             st.st_cast_from_f32(dq, storage, dq_low)
             st.st_cast_from_f32(dkv, storage, dkv_low)
+
+    step = step_team if team else step_ring
 
     for _ in range(args.warmup):
         step()
@@ -160,10 +238,11 @@ def main() -> int:
         step()
     kernels = st.st_profile_end()
 
-    fwd_flop, bwd_flop = si.algorithmic_flop(w)
+    met = order if team else None                          # chunks that earn FLOP (ring shape: all of them)
+    fwd_flop, bwd_flop = si.algorithmic_flop(w, met)
     total_flop = fwd_flop + bwd_flop
     value = total_flop / (ms_per_step * 1e-3) / 1e12
-    pairs = si.visible_pairs(w) * w.Hq * w.B
+    pairs = si.visible_pairs(w, met) * w.Hq * w.B
     # algorithmic work of each MFMA kernel per launch: forward = QK^T and PV; the dK/dV kernel owns
     # S, dP, dV, dK (four of the five backward contractions); the dQ kernel owns dQ (its recomputed
     # S and dP earn nothing)
@@ -193,36 +272,39 @@ def main() -> int:
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "Sq": w.Sq, "Sk": w.Sk,
                    "n_chunks": w.n_chunks, "causal": w.causal, "q_offset": w.q_offset, "mode": args.mode,
+                   "shape": args.shape,
                    "visit_order": f"P={w.ring_P},C={w.ring_C},rank={w.ring_rank}" if w.ring_P else "natural",
                    "passes": "fwd+bwd" if w.backward else "fwd"},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "algorithmic_tflop": {"fwd": round(fwd_flop / 1e12, 4), "bwd": round(bwd_flop / 1e12, 4)},
         "roofline": roofline,
         "kernels": per_kernel,
-        "merge_pass": merge_pass(st, torch, w),
+        "merge_pass": combine_pass(st, torch, states_o, states_l, n_own, w) if team else merge_pass(st, torch, w),
         "input_generation_s": round(gen_s, 1),
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inp)
+        out["cpu_baseline"] = cpu_baseline(w, inp, met)
     print(json.dumps(out))
     return 0
 
 
-def cpu_baseline(w, inp) -> dict:
+def cpu_baseline(w, inp, met=None) -> dict:
     """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of the same
-    workload: forward + backward of a few seeded query rows of the first KV group against all keys."""
+    workload: forward + backward of a few seeded query rows of the first KV group against all keys
+    (team shape: against the keys of the buffers this GPU meets)."""
     import synth_inputs as si
     from oracle import attention as oa
 
     rows_per_head = 128 if w.Sq >= 128 else w.Sq
     G = w.Hq // w.Hkv
     heads = list(range(min(G, w.Hq)))                      # the query heads of KV head 0
-    k_pos = [np.arange(w.Sk, dtype=np.int64) + w.k_offset(j) for j in range(w.n_chunks)]
+    met = list(range(w.n_chunks)) if met is None else list(met)
+    k_pos = [np.arange(w.Sk, dtype=np.int64) + w.k_offset(j) for j in met]
 
     def kv_head0(bits_list, f32_list):
         if w.dtype == "bf16":
-            return [si.bf16_bits_to_f32(b[:, :, 0:1, :]) for b in bits_list]
-        return [x[:, :, 0:1, :] for x in f32_list]
+            return [si.bf16_bits_to_f32(bits_list[j][:, :, 0:1, :]) for j in met]
+        return [f32_list[j][:, :, 0:1, :] for j in met]
 
     k0, v0 = kv_head0(inp.k_bits, inp.k), kv_head0(inp.v_bits, inp.v)
     pairs = 0
@@ -234,7 +316,10 @@ def cpu_baseline(w, inp) -> dict:
         oa.attention_forward(qh, k0, v0, q_pos, k_pos, w.causal, w.scale)
         if w.backward:
             oa.attention_backward(qh, k0, v0, inp.d_o[:, rows, h:h + 1, :], q_pos, k_pos, w.causal, w.scale)
-        pairs += int(np.clip(q_pos + 1, 0, w.N).sum()) if w.causal else len(rows) * w.N
+        if w.causal:
+            pairs += int(sum(np.clip(q_pos - w.k_offset(j) + 1, 0, w.Sk).sum() for j in met))
+        else:
+            pairs += len(rows) * w.Sk * len(met)
     secs = time.perf_counter() - t0
     flop = (4 + (10 if w.backward else 0)) * w.D * pairs * w.B
     try:
@@ -243,8 +328,8 @@ def cpu_baseline(w, inp) -> dict:
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": round(flop / secs / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"{rows_per_head} seeded query rows of each of {len(heads)} heads (KV head 0) against all "
-                      f"{w.N} keys, fwd{'+bwd' if w.backward else ''}, numpy fp64",
+            "sample": f"{rows_per_head} seeded query rows of each of {len(heads)} heads (KV head 0) against the "
+                      f"{w.Sk * len(met)} keys it meets, fwd{'+bwd' if w.backward else ''}, numpy fp64",
             "seconds": round(secs, 2)}
 
 

@@ -15,6 +15,8 @@
 // single owner: dQ is written once per launch, dK/dV once per workgroup, bit-reproducibly.
 #include <cstdlib>
 
+#include <utility>
+
 #include "st_internal.h"
 #include "st_mfma.h"
 
@@ -53,10 +55,10 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   const int n_qt = (s.Sq + kQ_BM - 1) / kQ_BM;
-  const int logical = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int qt = logical % n_qt;
-  const int h = (logical / n_qt) % s.Hq;
-  const int b = logical / (n_qt * s.Hq);
+  int qt, hb;
+  qtile_block(blockIdx.x, gridDim.x, n_qt, s.causal, qt, hb);
+  const int h = hb % s.Hq;
+  const int b = hb / s.Hq;
   const int hk = h / (s.Hq / s.Hkv);
 
   const int q_row0 = qt * kQ_BM + wave * kQ_WQ;
@@ -237,11 +239,13 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   const int g = lane >> 5, r = lane & 31;
   const int G = s.Hq / s.Hkv;
   const int n_kt = (s.Sk + kK_BK - 1) / kK_BK;
-  // logical order: chunk fastest, then key tile, then batch, KV head slowest: with the XCD mapping
-  // a KV head (and the Q, dO of its query heads) stays on one XCD's L2 when Hkv * B % 8 == 0
+  // logical order: key tile fastest, then chunk, then batch, KV head slowest: with the XCD mapping
+  // a KV head (and the Q, dO of its query heads) stays on one XCD's L2 when Hkv * B % 8 == 0.  The launcher
+  // sorts a causal table by position, so inside a head the workgroups come in order of falling work
+  // (earlier keys are seen by more query rows) and the tail of the launch stays short.
   const int logical = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int c = logical % a.t.n;
-  const int kt = (logical / a.t.n) % n_kt;
+  const int kt = logical % n_kt;
+  const int c = (logical / n_kt) % a.t.n;
   const int b = (logical / (a.t.n * n_kt)) % s.B;
   const int hk = logical / (a.t.n * n_kt * s.B);
 
@@ -472,6 +476,18 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
     return e ? atoi(e) : 1;
   }();
   a.dkv_fast = (fast_env && dkv_fast_usable(a)) ? 1 : 0;
+  if (a.s.causal) {
+    // earlier chunks first (the backward does not depend on the order of the table): their keys are seen by
+    // more query rows, and workgroups are handed out in table order
+    for (int i = 1; i < a.t.n; ++i)
+      for (int j = i; j > 0 && a.t.k_offset[j] < a.t.k_offset[j - 1]; --j) {
+        std::swap(a.t.k[j], a.t.k[j - 1]);
+        std::swap(a.t.v[j], a.t.v[j - 1]);
+        std::swap(a.t.k_offset[j], a.t.k_offset[j - 1]);
+        std::swap(a.dk[j], a.dk[j - 1]);
+        std::swap(a.dv[j], a.dv[j - 1]);
+      }
+  }
   {
     ProfScope prof(a.dkv_fast ? "bwd_dkv_edge" : "bwd_dkv_bf16", stream);
     if (a.s.D == 128) hipLaunchKernelGGL(bwd_dkv_bf16_kernel<128>, dim3((unsigned)total_k), dim3(256), 0, stream, a);

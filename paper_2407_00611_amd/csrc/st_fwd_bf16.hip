@@ -51,10 +51,10 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   const int g = lane >> 5, r = lane & 31;
 
   const int n_qt = (s.Sq + kBM - 1) / kBM;
-  const int logical = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int qt = logical % n_qt;
-  const int h = (logical / n_qt) % s.Hq;
-  const int b = logical / (n_qt * s.Hq);
+  int qt, hb;
+  qtile_block(blockIdx.x, gridDim.x, n_qt, s.causal, qt, hb);
+  const int h = hb % s.Hq;
+  const int b = hb / s.Hq;
   const int hk = h / (s.Hq / s.Hkv);
 
   // ---- Q fragments (B operand of S^T): query column r of block qb, d = 16 ks + 8 g .. +7
@@ -320,10 +320,10 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   const int n_qt = (s.Sq + kBM - 1) / kBM;
-  const int logical = xcd_logical_block(blockIdx.x, gridDim.x);
-  const int qt = logical % n_qt;
-  const int h = (logical / n_qt) % s.Hq;
-  const int b = logical / (n_qt * s.Hq);
+  int qt, hb;
+  qtile_block(blockIdx.x, gridDim.x, n_qt, s.causal, qt, hb);
+  const int h = hb % s.Hq;
+  const int b = hb / s.Hq;
   const int hk = h / (s.Hq / s.Hkv);
 
   const int q_row0 = qt * kBM + wave * kWQ;

@@ -277,4 +277,22 @@ __device__ __forceinline__ int xcd_logical_block(int id, int total) {
   return (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
 }
 
+// Block id -> (query tile, head-and-batch index) for the query-stationary kernels.  Every XCD gets a
+// contiguous range of heads (their K / V stay in that XCD's L2); inside the range the query tile is the
+// slow index and, under a causal mask, runs from the last tile down: later tiles see more keys, and
+// handing out the heaviest workgroups first keeps the tail of the launch short.
+__device__ __forceinline__ void qtile_block(int id, int total, int n_qt, int causal, int& qt, int& hb) {
+  const int n_hb = total / n_qt;
+  int qi;
+  if (n_hb % 8 == 0) {
+    const int per = n_hb / 8, j = id / 8;
+    hb = (id % 8) * per + j % per;
+    qi = j / per;
+  } else {
+    hb = id % n_hb;
+    qi = id / n_hb;
+  }
+  qt = causal ? n_qt - 1 - qi : qi;
+}
+
 }  // namespace st

@@ -18,7 +18,7 @@ from __future__ import annotations
 
 from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
-from typing import List, Optional
+from typing import List, Optional, Sequence
 
 import numpy as np
 
@@ -73,6 +73,15 @@ def paper_workloads() -> List[Workload]:
         Workload("cfg5_long_context", 5, "bf16", 1, 16, 16, 128, 8192, 8192, 64,
                  524288 - 8192, True, True, sigma=0.5, ring_P=64, ring_C=1, ring_rank=63),
     ]
+
+
+def team_workload() -> Workload:
+    """The model and layout of configuration 4 (GQA 32/8 heads, D = 128, 131072 tokens, P = 32 GPUs in teams
+    of C = 4) in the shape one GPU really sees in the concentric layout: the resident queries are the whole
+    team's C N/P = 16384 rows (last team), the keys / values are the P/C = 8 gathered team buffers of 16384
+    tokens, of which a GPU meets P/C^2 = 2."""
+    return Workload("team4x8_gqa_gathered", 6, "bf16", 1, 32, 8, 128, 16384, 16384, 8, 131072 - 16384, True, True,
+                    ring_P=32, ring_C=4, ring_rank=31)
 
 
 def small_workload(name="small", dtype="bf16", B=1, Hq=2, Hkv=1, D=128, Sq=192, Sk=160,
@@ -173,15 +182,17 @@ def sampled_rows(w: Workload, head: int, count: int = 256) -> np.ndarray:
     return np.unique(rows).astype(np.int64)
 
 
-def visible_pairs(w: Workload) -> int:
-    """Exact number of (query, key) pairs per head that the mask leaves visible."""
+def visible_pairs(w: Workload, chunks: Optional[Sequence[int]] = None) -> int:
+    """Exact number of (query, key) pairs per head that the mask leaves visible, over all chunks or
+    over the listed ones."""
+    chunks = range(w.n_chunks) if chunks is None else chunks
     if not w.causal:
-        return w.Sq * w.N
+        return w.Sq * w.Sk * len(chunks)
     i = np.arange(w.Sq, dtype=np.int64) + w.q_offset
-    return int(np.clip(i + 1, 0, w.N).sum())
+    return int(sum(np.clip(i - w.k_offset(j) + 1, 0, w.Sk).sum() for j in chunks))
 
 
-def algorithmic_flop(w: Workload):
+def algorithmic_flop(w: Workload, chunks: Optional[Sequence[int]] = None):
     """(fwd, bwd) FLOP: two contractions forward and five backward over visible pairs."""
-    pairs = visible_pairs(w) * w.Hq * w.B
+    pairs = visible_pairs(w, chunks) * w.Hq * w.B
     return 4 * w.D * pairs, (10 * w.D * pairs if w.backward else 0)
