@@ -10,7 +10,9 @@ The workload is benchmark configuration 4 (GQA 32/8 heads, D=128, Q shard 4096, 
 
 `--shape team` times the same model in the shape one GPU of the concentric layout really sees (the team's
 gathered 16384 queries against the two gathered team buffers this GPU meets, then the 4-way combine that
-keeps its own 4096 rows; backward of the same shape); the default `--shape ring` is the headline workload.
+keeps its own 4096 rows; backward of the same shape); `--shape dit` times a ring share shaped like the
+paper's diffusion-transformer runs (24 heads of size 64, full mask, 16384-token shard of 131072 tokens);
+the default `--shape ring` is the headline workload.
 
 Prints ONE JSON line (see the keys below).  `value` is algorithmic attention TFLOP/s: 4*D per
 visible (query, key) pair forward and 10*D backward, masked pairs and recomputation earn nothing.
@@ -104,9 +106,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4)")
     ap.add_argument("--mode", choices=["fused", "stepwise"], default="fused")
-    ap.add_argument("--shape", choices=["ring", "team"], default="ring",
+    ap.add_argument("--shape", choices=["ring", "team", "dit"], default="ring",
                     help="ring: a resident N/P-row shard meets every chunk (configurations 1..5); "
-                         "team: the team-gathered shape of the concentric layout (model of configuration 4)")
+                         "team: the team-gathered shape of the concentric layout (model of configuration 4); "
+                         "dit: a ring share shaped like the paper's diffusion-transformer runs (24 heads x 64, full mask)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -124,7 +127,7 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     team = args.shape == "team"
-    w = si.team_workload() if team else si.paper_workloads()[args.config - 1]
+    w = si.team_workload() if team else si.dit_workload() if args.shape == "dit" else si.paper_workloads()[args.config - 1]
     mode = st.ST_RING_FUSED if args.mode == "fused" else st.ST_RING_STEPWISE
     bf16 = w.dtype == "bf16"
     storage = st.ST_BF16 if bf16 else st.ST_F32

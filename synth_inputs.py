@@ -84,6 +84,14 @@ def team_workload() -> Workload:
                     ring_P=32, ring_C=4, ring_rank=31)
 
 
+def dit_workload() -> Workload:
+    """A share shaped like the paper's diffusion-transformer runs (model table: DiT 1B, 24 heads, hidden 1536,
+    i.e. head size 64; full mask; scaling runs at 128K tokens on 8 GPUs): rank 3 of a ring of 8, 16384-token
+    shard, 8 chunks of 16384 tokens, non-causal, bf16."""
+    return Workload("dit1b_full_mask_ring8", 7, "bf16", 1, 24, 24, 64, 16384, 16384, 8, 3 * 16384, False, True,
+                    ring_P=8, ring_C=1, ring_rank=3)
+
+
 def small_workload(name="small", dtype="bf16", B=1, Hq=2, Hkv=1, D=128, Sq=192, Sk=160,
                    n_chunks=3, q_offset=None, causal=True, cfg=90, sigma=1.0) -> Workload:
     """A ragged multi-tile case the oracle finishes in well under a second."""

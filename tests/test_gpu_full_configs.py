@@ -1,5 +1,6 @@
-"""GPU parity at the full benchmark sizes (configurations 3, 4 and 5), in the launch configuration
-bench.py times: fused ring forward, then fused ring backward, chunks visited in the ring's order.
+"""GPU parity at the full benchmark sizes (configurations 3, 4 and 5, and the diffusion-transformer-shaped
+share bench.py --shape dit times), in the launch configuration bench.py times: fused ring forward, then
+fused ring backward, chunks visited in the ring's order.
 
 The fp64 oracle cannot do these sizes in full, so it does seeded sampled query rows of every head
 against ALL keys:
@@ -20,17 +21,18 @@ from util import assert_close, bits_dev, host
 
 pytestmark = pytest.mark.gpu
 
-# configuration -> sampled rows per head (configuration 5: the 256 rows its definition names)
-CASES = {3: 128, 4: 64, 5: 256}
+# workload -> sampled rows per head (configuration 5: the 256 rows its definition names)
+CASES = {"cfg3": (lambda: si.paper_workloads()[2], 128), "cfg4": (lambda: si.paper_workloads()[3], 64),
+         "cfg5": (lambda: si.paper_workloads()[4], 256), "dit": (si.dit_workload, 64)}
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("cfg", sorted(CASES), ids=[f"cfg{c}" for c in sorted(CASES)])
+@pytest.mark.parametrize("cfg", list(CASES))
 def test_full_size_sampled_rows(cfg):
-    w = si.paper_workloads()[cfg - 1]
-    n_rows = CASES[cfg]
+    w = CASES[cfg][0]()
+    n_rows = CASES[cfg][1]
     G = w.Hq // w.Hkv
-    print(f"[cfg{cfg}] generating inputs", flush=True)
+    print(f"[{cfg}] generating inputs", flush=True)
     inp = si.make_inputs(w, threads=16, keep_f32=False)
     q = bits_dev(inp.q_bits)
     d_o = bits_dev(inp.d_o_bits)
@@ -40,7 +42,7 @@ def test_full_size_sampled_rows(cfg):
     order, members = st.st_visit_order(w.ring_P, w.ring_C, w.ring_rank)
     rows = [si.sampled_rows(w, h, n_rows) for h in range(w.Hq)]
 
-    print(f"[cfg{cfg}] GPU forward + backward, run A (dense dO)", flush=True)
+    print(f"[{cfg}] GPU forward + backward, run A (dense dO)", flush=True)
     o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, st.ST_RING_FUSED)
     dq = torch.zeros_like(o)
     dk = [torch.zeros(k.shape, device="cuda") for k in ks]
@@ -53,7 +55,7 @@ def test_full_size_sampled_rows(cfg):
     assert torch.equal(o_low, o.to(torch.bfloat16))
     del dk, dv
 
-    print(f"[cfg{cfg}] GPU backward, run B (dO zero outside the sampled rows)", flush=True)
+    print(f"[{cfg}] GPU backward, run B (dO zero outside the sampled rows)", flush=True)
     keep = torch.zeros((w.B, w.Sq, w.Hq, 1), dtype=torch.bool, device="cuda")
     for h in range(w.Hq):
         keep[:, torch.from_numpy(rows[h]).cuda(), h] = True
@@ -77,7 +79,7 @@ def test_full_size_sampled_rows(cfg):
         dk_ref = [np.zeros((w.B, w.Sk, 1, w.D)) for _ in range(w.n_chunks)]
         dv_ref = [np.zeros((w.B, w.Sk, 1, w.D)) for _ in range(w.n_chunks)]
         for h in range(g * G, (g + 1) * G):
-            print(f"[cfg{cfg}] oracle: head {h} ({len(rows[h])} rows x {w.N} keys)", flush=True)
+            print(f"[{cfg}] oracle: head {h} ({len(rows[h])} rows x {w.N} keys)", flush=True)
             q_pos = rows[h] + w.q_offset
             qh = inp.q[:, rows[h], h:h + 1, :]
             doh = inp.d_o[:, rows[h], h:h + 1, :]
