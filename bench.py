@@ -12,6 +12,8 @@ The workload is benchmark configuration 4 (GQA 32/8 heads, D=128, Q shard 4096, 
 gathered 16384 queries against the two gathered team buffers this GPU meets, then the 4-way combine that
 keeps its own 4096 rows; backward of the same shape); `--shape dit` times a ring share shaped like the
 paper's diffusion-transformer runs (24 heads of size 64, full mask, 16384-token shard of 131072 tokens);
+`--shape zigzag [--rank r]` times the model of configuration 4 under the load-balanced causal placement (rank
+r holds pieces r and 63 - r of the sequence cut in 64);
 the default `--shape ring` is the headline workload.
 
 Prints ONE JSON line (see the keys below).  `value` is algorithmic attention TFLOP/s: 4*D per
@@ -106,10 +108,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4)")
     ap.add_argument("--mode", choices=["fused", "stepwise"], default="fused")
-    ap.add_argument("--shape", choices=["ring", "team", "dit"], default="ring",
+    ap.add_argument("--shape", choices=["ring", "team", "dit", "zigzag"], default="ring",
                     help="ring: a resident N/P-row shard meets every chunk (configurations 1..5); "
                          "team: the team-gathered shape of the concentric layout (model of configuration 4); "
-                         "dit: a ring share shaped like the paper's diffusion-transformer runs (24 heads x 64, full mask)")
+                         "dit: a ring share shaped like the paper's diffusion-transformer runs (24 heads x 64, full mask); "
+                         "zigzag: the model of configuration 4 under the load-balanced causal placement (--rank picks the rank)")
+    ap.add_argument("--rank", type=int, default=0, help="rank of the ring for --shape zigzag (0..31)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -127,7 +131,8 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     team = args.shape == "team"
-    w = si.team_workload() if team else si.dit_workload() if args.shape == "dit" else si.paper_workloads()[args.config - 1]
+    w = si.team_workload() if team else si.dit_workload() if args.shape == "dit" else si.zigzag_workload(args.rank) if args.shape == "zigzag" \
+        else si.paper_workloads()[args.config - 1]
     mode = st.ST_RING_FUSED if args.mode == "fused" else st.ST_RING_STEPWISE
     bf16 = w.dtype == "bf16"
     storage = st.ST_BF16 if bf16 else st.ST_F32
@@ -148,6 +153,10 @@ def main() -> int:
     koffs = [w.k_offset(j) for j in range(w.n_chunks)]
     if team:
         order, members = st.st_team_visit_order(w.ring_P, w.ring_C, w.ring_rank), None
+    elif w.q_seg:
+        # rank r holds pieces r and 2 P - 1 - r; the ring delivers rank (r - i) mod P's two pieces at step i
+        ranks = st.st_visit_order(w.ring_P, 1, w.ring_rank)[0]
+        order, members = [c for x in ranks for c in (x, 2 * w.ring_P - 1 - x)], None
     elif w.ring_P:
         order, members = st.st_visit_order(w.ring_P, w.ring_C, w.ring_rank)
     else:
@@ -159,10 +168,10 @@ def main() -> int:
     o_acc = torch.empty((w.B, w.Sq, w.Hq, w.D), dtype=torch.float32, device=dev)
     lse = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device=dev)
     o_low = torch.empty((w.B, w.Sq, w.Hq, w.D), dtype=q.dtype, device=dev)
-    ws_f = torch.empty(st.st_ring_workspace_bytes(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, mode, False) + 256,
+    ws_f = torch.empty(st.st_ring_workspace_bytes(q, ks, vs, w.q_where, koffs, w.causal, w.scale, mode, False) + 256,
                        dtype=torch.uint8, device=dev)
     if w.backward:
-        ws_b = torch.empty(st.st_ring_workspace_bytes(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, mode, True) + 256,
+        ws_b = torch.empty(st.st_ring_workspace_bytes(q, ks, vs, w.q_where, koffs, w.causal, w.scale, mode, True) + 256,
                            dtype=torch.uint8, device=dev)
         dq = torch.empty_like(o_acc)
         dkv = torch.empty((2, w.n_chunks) + tuple(ks[0].shape), dtype=torch.float32, device=dev)
@@ -181,13 +190,13 @@ def main() -> int:
             if a == a_r:
                 continue
             ob = st.st_team_visit_order(w.ring_P, w.ring_C, w.ring_rank - a_r + a)
-            o_x, l_x, _ = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, ob, None, mode,
+            o_x, l_x, _ = st.st_ring_fwd(q, ks, vs, w.q_where, koffs, w.causal, w.scale, ob, None, mode,
                                          want_lowp=False, workspace=ws_f)
             others.append((o_x, l_x))
         o_own = torch.empty((w.B, n_own, w.Hq, w.D), dtype=torch.float32, device=dev)
         lse_own = torch.empty((w.B, w.Hq, n_own), dtype=torch.float32, device=dev)
         o_own_low = torch.empty((w.B, n_own, w.Hq, w.D), dtype=q.dtype, device=dev)
-        st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, mode, o_acc=o_acc, lse=lse,
+        st.st_ring_fwd(q, ks, vs, w.q_where, koffs, w.causal, w.scale, order, None, mode, o_acc=o_acc, lse=lse,
                        want_lowp=False, workspace=ws_f)
         states_o = [o_acc] + [x[0] for x in others]
         states_l = [lse] + [x[1] for x in others]
@@ -196,7 +205,7 @@ def main() -> int:
         del o_team
 
     def step_team():
-        st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, mode,
+        st.st_ring_fwd(q, ks, vs, w.q_where, koffs, w.causal, w.scale, order, None, mode,
                        o_acc=o_acc, lse=lse, want_lowp=False, workspace=ws_f)
         st.st_attn_combine(states_o, states_l, a_r * n_own, n_own, storage, o_out=o_own, lse_out=lse_own,
                            o_out_lowp=o_own_low)
@@ -204,7 +213,7 @@ def main() -> int:
             dq.zero_()
             for j in order:
                 dkv[:, j].zero_()
-            st.st_ring_bwd(q, ks, vs, d_o, o_team_low, lse_team, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv,
+            st.st_ring_bwd(q, ks, vs, d_o, o_team_low, lse_team, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
                            mode, workspace=ws_b)
             st.st_cast_from_f32(dq, storage, dq_low)
             for j in order:
@@ -212,12 +221,12 @@ def main() -> int:
                 st.st_cast_from_f32(dkv[1, j], storage, dkv_low[1, j])
 
     def step_ring():
-        st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, mode,
+        st.st_ring_fwd(q, ks, vs, w.q_where, koffs, w.causal, w.scale, order, members, mode,
                        o_acc=o_acc, lse=lse, o_lowp=o_low, workspace=ws_f)
         if w.backward:
             dq.zero_()
             dkv.zero_()
-            st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv,
+            st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
                            mode, workspace=ws_b)
             st.st_cast_from_f32(dq, storage, dq_low)
             st.st_cast_from_f32(dkv, storage, dkv_low)
@@ -274,7 +283,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "Sq": w.Sq, "Sk": w.Sk,
-                   "n_chunks": w.n_chunks, "causal": w.causal, "q_offset": w.q_offset, "mode": args.mode,
+                   "n_chunks": w.n_chunks, "causal": w.causal, "q_offset": w.q_offset, "q_seg": w.q_seg, "q_offset2": w.q_offset2, "mode": args.mode,
                    "shape": args.shape,
                    "visit_order": f"P={w.ring_P},C={w.ring_C},rank={w.ring_rank}" if w.ring_P else "natural",
                    "passes": "fwd+bwd" if w.backward else "fwd"},
@@ -314,7 +323,7 @@ def cpu_baseline(w, inp, met=None) -> dict:
     t0 = time.perf_counter()
     for h in heads:
         rows = si.sampled_rows(w, h, rows_per_head)
-        q_pos = rows + w.q_offset
+        q_pos = w.q_positions()[rows]
         qh = inp.q[:, rows, h:h + 1, :]
         oa.attention_forward(qh, k0, v0, q_pos, k_pos, w.causal, w.scale)
         if w.backward:

@@ -76,8 +76,12 @@ typedef struct {
   int32_t Sq, Sk;           /* tokens in the Q shard / in this chunk; Sk may be 0 */
   int64_t q_offset;         /* global position of Q row 0 */
   int64_t k_offset;         /* global position of chunk row 0 */
-  int32_t causal;           /* 0: every key visible; 1: visible iff k_offset+t <= q_offset+i */
+  int32_t causal;           /* 0: every key visible; 1: visible iff k_offset+t <= position of query row i */
   float   scale;            /* softmax scale, finite and > 0, normally 1/sqrt(D) (Section 2.1 attention equation) */
+  int32_t q_seg;            /* 0: the Q rows are one run from q_offset.  > 0: rows [q_seg, Sq) are a second run */
+  int64_t q_offset2;        /*    whose row q_seg sits at q_offset2 >= q_offset + q_seg (appendix "Sequence
+                             *    Parallelism Dataloader": a rank holds an early and a late piece of the sequence so
+                             *    that causal work is equal across ranks); 0 < q_seg < Sq */
 } st_block_desc;
 
 /* One GPU's whole share: the Q shard plus the table of chunks the ring delivers
@@ -96,6 +100,8 @@ typedef struct {
   int64_t k_stride_b, k_stride_s, k_stride_h;   /* shared by all K chunks */
   int64_t v_stride_b, v_stride_s, v_stride_h;   /* shared by all V chunks */
   const int64_t* k_offset;  /* host array [n_chunks]: global position of row 0 of chunk j */
+  int32_t q_seg;            /* second run of query rows, as in st_block_desc (0: none) */
+  int64_t q_offset2;
 } st_ring_desc;
 
 /* ---- ring iteration, forward (Algorithm 1: forward_iteration before its fold) ----

@@ -32,7 +32,7 @@ class st_tensor(C.Structure):
 class st_block_desc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
                 ("Sq", C.c_int32), ("Sk", C.c_int32), ("q_offset", C.c_int64), ("k_offset", C.c_int64),
-                ("causal", C.c_int32), ("scale", C.c_float)]
+                ("causal", C.c_int32), ("scale", C.c_float), ("q_seg", C.c_int32), ("q_offset2", C.c_int64)]
 
 
 class st_ring_desc(C.Structure):
@@ -42,7 +42,7 @@ class st_ring_desc(C.Structure):
                 ("k_ptr", C.POINTER(C.c_void_p)), ("v_ptr", C.POINTER(C.c_void_p)),
                 ("k_stride_b", C.c_int64), ("k_stride_s", C.c_int64), ("k_stride_h", C.c_int64),
                 ("v_stride_b", C.c_int64), ("v_stride_s", C.c_int64), ("v_stride_h", C.c_int64),
-                ("k_offset", C.POINTER(C.c_int64))]
+                ("k_offset", C.POINTER(C.c_int64)), ("q_seg", C.c_int32), ("q_offset2", C.c_int64)]
 
 
 class st_comm_report(C.Structure):
@@ -144,10 +144,20 @@ def _f32_dense(t: torch.Tensor, shape, name: str) -> torch.Tensor:
     return t
 
 
+def _q_runs(q_offset) -> Tuple[int, int, int]:
+    """q_offset is the position of query row 0, or (position of row 0, rows in the first run, position of the
+    first row of the second run) for a shard made of two runs of the sequence."""
+    if isinstance(q_offset, (tuple, list)):
+        off, seg, off2 = q_offset
+        return int(off), int(seg), int(off2)
+    return int(q_offset), 0, 0
+
+
 def _block_desc(q, k, q_offset, k_offset, causal, scale) -> st_block_desc:
     B, Sq, Hq, D = q.shape
-    return st_block_desc(_dtype_code(q), B, Hq, k.shape[2], D, Sq, k.shape[1], int(q_offset), int(k_offset),
-                         1 if causal else 0, float(scale))
+    off, seg, off2 = _q_runs(q_offset)
+    return st_block_desc(_dtype_code(q), B, Hq, k.shape[2], D, Sq, k.shape[1], off, int(k_offset),
+                         1 if causal else 0, float(scale), seg, off2)
 
 
 def st_version() -> int:
@@ -300,11 +310,12 @@ class _Ring:
         self.k_ptr = (C.c_void_p * n)(*[k.data_ptr() for k in k_chunks])
         self.v_ptr = (C.c_void_p * n)(*[v.data_ptr() for v in v_chunks])
         self.k_off = (C.c_int64 * n)(*[int(x) for x in k_offsets])
-        self.desc = st_ring_desc(_dtype_code(q), B, Hq, k0.shape[2], D, Sq, k0.shape[1], int(q_offset),
+        off, seg, off2 = _q_runs(q_offset)
+        self.desc = st_ring_desc(_dtype_code(q), B, Hq, k0.shape[2], D, Sq, k0.shape[1], off,
                                  1 if causal else 0, float(scale), n,
                                  C.cast(self.k_ptr, C.POINTER(C.c_void_p)), C.cast(self.v_ptr, C.POINTER(C.c_void_p)),
                                  k0.stride(0), k0.stride(1), k0.stride(2), v0.stride(0), v0.stride(1), v0.stride(2),
-                                 C.cast(self.k_off, C.POINTER(C.c_int64)))
+                                 C.cast(self.k_off, C.POINTER(C.c_int64)), seg, off2)
 
 
 def st_ring_workspace_bytes(q, k_chunks, v_chunks, q_offset, k_offsets, causal, scale, mode: int,

@@ -82,10 +82,18 @@ st_status check_f32(const char* name, const void* p, int64_t n_elems) {
 st::View view_of(const st_tensor* t) { return st::View{t->ptr, t->stride_b, t->stride_s, t->stride_h}; }
 
 st::Shape shape_of(const st_block_desc* d) {
-  return st::Shape{d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk, d->q_offset, d->causal ? 1 : 0, d->scale};
+  return st::Shape{d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk, d->q_offset, d->causal ? 1 : 0, d->scale, d->q_seg, d->q_offset2};
 }
 st::Shape shape_of(const st_ring_desc* d) {
-  return st::Shape{d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk, d->q_offset, d->causal ? 1 : 0, d->scale};
+  return st::Shape{d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk, d->q_offset, d->causal ? 1 : 0, d->scale, d->q_seg, d->q_offset2};
+}
+
+// two runs of query rows: the second must not start before the first ends (positions rise with the row index)
+st_status check_segments(int32_t Sq, int64_t q_offset, int32_t q_seg, int64_t q_offset2) {
+  if (q_seg == 0) return ST_OK;
+  if (q_seg < 0 || q_seg >= Sq) return fail(ST_ERR_INVALID_ARG, "q_seg = %d must be 0 or inside the %d query rows", q_seg, Sq);
+  if (q_offset2 < q_offset + q_seg) return fail(ST_ERR_INVALID_ARG, "second run of query rows starts before the first ends");
+  return ST_OK;
 }
 
 #define ST_TRY(expr)                  \
@@ -108,13 +116,14 @@ hipError_t launch_bwd(int dtype, const st::BwdArgs& a, hipStream_t s) {
 
 // chunk lies entirely in the causal future of the shard: nothing to compute
 inline bool chunk_invisible(const st_ring_desc* d, int j) {
-  return d->Sk == 0 || (d->causal && d->k_offset[j] > d->q_offset + d->Sq - 1);
+  return d->Sk == 0 || (d->causal && d->k_offset[j] > st::q_pos(shape_of(d), d->Sq - 1));
 }
 
 st_status check_ring(const st_ring_desc* d, const st_tensor* q, const int32_t* order, int32_t n_visit) {
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
   ST_TRY(check_scale(d->scale));
+  ST_TRY(check_segments(d->Sq, d->q_offset, d->q_seg, d->q_offset2));
   if (d->n_chunks < 1 || d->n_chunks > ST_MAX_CHUNKS) return fail(ST_ERR_INVALID_ARG, "n_chunks must be in 1..%d", ST_MAX_CHUNKS);
   if (!d->k_ptr || !d->v_ptr || !d->k_offset) return fail(ST_ERR_INVALID_ARG, "null chunk table");
   if (n_visit < 0 || n_visit > d->n_chunks) return fail(ST_ERR_INVALID_ARG, "n_visit out of range");
@@ -225,6 +234,7 @@ st_status st_attn_block_fwd(const st_block_desc* d, const st_tensor* q, const st
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
   ST_TRY(check_scale(d->scale));
+  ST_TRY(check_segments(d->Sq, d->q_offset, d->q_seg, d->q_offset2));
   const int64_t n_q = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
   ST_TRY(check_tensor("q", q, d->dtype, n_q));
   ST_TRY(check_tensor("k", k, d->dtype, n_kv));
@@ -313,6 +323,7 @@ st_status st_attn_block_bwd(const st_block_desc* d, const st_tensor* q, const st
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
   ST_TRY(check_scale(d->scale));
+  ST_TRY(check_segments(d->Sq, d->q_offset, d->q_seg, d->q_offset2));
   const int64_t n_q = (int64_t)d->B * d->Sq * d->Hq * d->D, n_kv = (int64_t)d->B * d->Sk * d->Hkv * d->D;
   ST_TRY(check_tensor("q", q, d->dtype, n_q));
   ST_TRY(check_tensor("d_o", d_o, d->dtype, n_q));
@@ -324,7 +335,7 @@ st_status st_attn_block_bwd(const st_block_desc* d, const st_tensor* q, const st
   ST_TRY(check_f32("dk_acc", dk_acc, n_kv));
   ST_TRY(check_f32("dv_acc", dv_acc, n_kv));
   if (n_q == 0 || n_kv == 0) return ST_OK;
-  if (d->causal && d->k_offset > d->q_offset + d->Sq - 1) return ST_OK;   // chunk entirely in the future
+  if (d->causal && d->k_offset > st::q_pos(shape_of(d), d->Sq - 1)) return ST_OK;   // chunk entirely in the future
   st::BwdArgs a;
   memset(&a, 0, sizeof(a));
   a.s = shape_of(d);

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = q_row0 + 32 * qb + r;
-    qpos[qb] = s.q_offset + i;
+    qpos[qb] = q_pos(s, i);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       qf[qb][ks] = global_frag(qbase, a.q.ss, i, s.Sq, ks, g);
@@ -100,14 +100,14 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
   const float c_exp = s.scale * kLog2e;
 
   auto chunk_tiles = [&](int c) -> int {
-    const int nv = visible_keys(s.causal, s.Sk, s.q_offset + wg_last_row, a.t.k_offset[c]);
+    const int nv = visible_keys(s.causal, s.Sk, q_pos(s, wg_last_row), a.t.k_offset[c]);
     return (nv + kQ_BN - 1) / kQ_BN;
   };
   // first tile of a chunk that is this kernel's: the leading ones may belong to the fast kernel
   const int fast_row0 = qt * kQ_BM / kDqFastRows * kDqFastRows;
   const bool fast_on = a.dq_fast && kQ_BN == kDqFastKeys && fast_row0 + kDqFastRows <= s.Sq;
   auto chunk_t0 = [&](int c) -> int {
-    return fast_on ? dq_fast_tiles(s.causal, s.Sk, s.q_offset, fast_row0, a.t.k_offset[c]) : 0;
+    return fast_on ? dq_fast_tiles(s, fast_row0, a.t.k_offset[c]) : 0;
   };
   int c_cur = 0, t_cur = 0, n_cur = 0;
   while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) <= (t_cur = chunk_t0(c_cur))) ++c_cur;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
 
     const int64_t k0 = a.t.k_offset[c_cur];
     const int tile_k0 = t_cur * kQ_BN;
-    const int nv_wave_min = visible_keys(s.causal, s.Sk, s.q_offset + wave_first_row, k0);
+    const int nv_wave_min = visible_keys(s.causal, s.Sk, q_pos(s, wave_first_row), k0);
     const ST_LDS char* ktile = smem + buf * 2 * kTile;
     const ST_LDS char* vtile = ktile + kTile;
 #pragma unroll
@@ -256,9 +256,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   // first query row that can see the first key of this workgroup / wavefront
   int wg_i0 = 0;
   if (s.causal) {
-    const int64_t d = k0 + wg_key0 - s.q_offset;
-    if (d >= s.Sq) return;
-    wg_i0 = d > 0 ? (int)d : 0;
+    wg_i0 = q_row_of(s, k0 + wg_key0);
+    if (wg_i0 >= s.Sq) return;
   }
   const int q_tile_first = wg_i0 / kK_BQ;
   const int n_q_tiles = (s.Sq + kK_BQ - 1) / kK_BQ;
@@ -269,7 +268,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
   if (a.dkv_fast && kK_BQ == kDkvFastRows) {
     const int tile_key0 = wg_key0 / kDkvFastKeys * kDkvFastKeys;
     if (tile_key0 + kDkvFastKeys <= s.Sk) {
-      const int fb = dkv_fast_first_block(s.causal, s.q_offset, k0, tile_key0), n_full = s.Sq / kDkvFastRows;
+      const int fb = dkv_fast_first_block(s, k0, tile_key0), n_full = s.Sq / kDkvFastRows;
       if (fb < n_full) {
         q_split = fb > q_tile_first ? fb : q_tile_first;
         q_resume = n_full;
@@ -288,9 +287,9 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
       kf[nb][ks] = global_frag(kbase, a.t.kss, wave_key0 + 32 * nb + r, s.Sk, ks, g);
       vf[nb][ks] = global_frag(vbase, a.t.vss, wave_key0 + 32 * nb + r, s.Sk, ks, g);
     }
-  int64_t kpos_rel[NB];   // key position minus q_offset: query row i sees the key iff i >= kpos_rel
+  int kpos_rel[NB];       // first query row that sees the key: row i sees it iff i >= kpos_rel
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) kpos_rel[nb] = k0 + wave_key0 + 32 * nb + r - s.q_offset;
+  for (int nb = 0; nb < NB; ++nb) kpos_rel[nb] = q_row_of(s, k0 + wave_key0 + 32 * nb + r);
 
   f32x16 acc_k[DB][NB], acc_v[DB][NB];
 #pragma unroll
@@ -387,10 +386,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
           drow[j] = *reinterpret_cast<const ST_LDS f32x4*>(dlt_s + 32 * qb + 8 * j + 4 * g);
         }
         // wave-uniform: is some (row, key) pair of this block masked?
-        const bool need_mask = s.causal && (s.q_offset + blk_i0 < k0 + wave_key0 + kK_WK - 1);
+        const bool need_mask = s.causal && (q_pos(s, blk_i0) < k0 + wave_key0 + kK_WK - 1);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          const int64_t first_row = kpos_rel[nb] - blk_i0;     // block row index from which the key is visible
+          const int first_row = kpos_rel[nb] - blk_i0;     // block row index from which the key is visible
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             float p = __builtin_amdgcn_exp2f(fmaf(sc[nb][v], c_exp, -lrow[v / 4][v % 4]));

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kWaves * 64) void fwd_f32_kernel(const FwdArgs a) {
   __syncthreads();
   if (!live) return;
 
-  const int64_t qpos = s.q_offset + i;
+  const int64_t qpos = q_pos(s, i);
   float m = -INFINITY, l = 0.f, acc[kDV] = {0.f, 0.f, 0.f, 0.f};
   for (int c = 0; c < a.t.n; ++c) {
     const float* kb = (const float*)a.t.k[c] + b * a.t.ksb + g * a.t.ksh;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_dq_f32_kernel(const BwdArgs a
   const int64_t stat = ((int64_t)b * s.Hq + h) * s.Sq + i;
   const float lse = a.lse[stat], dl = a.delta[stat];
   if (lse == -INFINITY) return;                            // empty row: no gradient
-  const int64_t qpos = s.q_offset + i;
+  const int64_t qpos = q_pos(s, i);
   float acc[kDV] = {0.f, 0.f, 0.f, 0.f};
   for (int c = 0; c < a.t.n; ++c) {
     const float* kb = (const float*)a.t.k[c] + b * a.t.ksb + g * a.t.ksh;
@@ -181,9 +181,8 @@ __global__ __launch_bounds__(kWaves * 64) void bwd_dkv_f32_kernel(const BwdArgs 
   const int64_t kpos = a.t.k_offset[c] + t;
   int i_first = 0;                                          // first query row that sees this key
   if (s.causal) {
-    const int64_t d = kpos - s.q_offset;
-    if (d >= s.Sq) return;
-    i_first = d > 0 ? (int)d : 0;
+    i_first = q_row_of(s, kpos);
+    if (i_first >= s.Sq) return;
   }
   float acc_k[kDV] = {0.f, 0.f, 0.f, 0.f}, acc_v[kDV] = {0.f, 0.f, 0.f, 0.f};
   for (int hh = 0; hh < G; ++hh) {

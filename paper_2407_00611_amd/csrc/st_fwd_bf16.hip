@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = q_row0 + 32 * qb + r;
-    qpos[qb] = s.q_offset + i;
+    qpos[qb] = q_pos(s, i);
     const char* qrow = (const char*)a.q.ptr + ((int64_t)b * a.q.sb + (int64_t)i * a.q.ss + (int64_t)h * a.q.sh) * 2;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   // ---- flattened (chunk, tile) walk with one-tile lookahead
   // number of tiles the workgroup needs from chunk c: up to the last key its last row may see
   auto chunk_tiles = [&](int c) -> int {
-    const int nv = visible_keys(s.causal, s.Sk, s.q_offset + wg_last_row, a.t.k_offset[c]);
+    const int nv = visible_keys(s.causal, s.Sk, q_pos(s, wg_last_row), a.t.k_offset[c]);
     return (nv + kBN - 1) / kBN;
   };
   // first tile of a chunk that is this kernel's: the leading ones may belong to the fast kernel, whose
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   const int fast_row0 = qt * kBM / kQTileFastRows * kQTileFastRows;
   const bool fast_on = a.fwd_fast && kBN == kQTileFastKeys && fast_row0 + kQTileFastRows <= s.Sq;
   auto chunk_t0 = [&](int c) -> int {
-    return fast_on ? qtile_fast_tiles(s.causal, s.Sk, s.q_offset, fast_row0, a.t.k_offset[c]) : 0;
+    return fast_on ? qtile_fast_tiles(s, fast_row0, a.t.k_offset[c]) : 0;
   };
   bool fast_wrote = false;
   if (fast_on)
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     const int64_t k0 = a.t.k_offset[c_cur];
     const int tile_k0 = t_cur * kBN;
     // visible-prefix lengths: first / last live row of the wavefront and this lane's rows
-    const int nv_wave_min = visible_keys(s.causal, s.Sk, s.q_offset + wave_first_row, k0);
+    const int nv_wave_min = visible_keys(s.causal, s.Sk, q_pos(s, wave_first_row), k0);
     {  // every wavefront computes every tile the workgroup walks; rows that see nothing of it are masked
       const ST_LDS char* ktile = smem + buf * 2 * kTile;
       const ST_LDS char* vtile = ktile + kTile;
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = q_row0 + 32 * qb + r;
-    qpos[qb] = s.q_offset + i;
+    qpos[qb] = q_pos(s, i);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = global_frag(qbase, a.q.ss, i, s.Sq, ks, g);
   }
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
 
   // ---- tile walk: cursors for the tile in softmax / PV (cur), in S (nxt) and in flight by DMA (dma)
   auto chunk_tiles = [&](int c) -> int {
-    const int nv = visible_keys(s.causal, s.Sk, s.q_offset + wg_last_row, a.t.k_offset[c]);
+    const int nv = visible_keys(s.causal, s.Sk, q_pos(s, wg_last_row), a.t.k_offset[c]);
     return (nv + kBN - 1) / kBN;
   };
   auto first_tile = [&]() -> TileCursor {
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
     auto mask_block = [&](f32x16 (&sc)[QB], const TileCursor& x, int kb) {
       const int64_t k0 = a.t.k_offset[x.c];
       const int blk_k0 = x.t * kBN + 32 * kb;
-      const int nv_min = visible_keys(s.causal, s.Sk, s.q_offset + wave_first_row, k0);
+      const int nv_min = visible_keys(s.causal, s.Sk, q_pos(s, wave_first_row), k0);
       if (blk_k0 + 32 > nv_min) {                                // wave-uniform, rare
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)

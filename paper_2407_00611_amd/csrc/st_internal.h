@@ -18,10 +18,28 @@ struct View {                   // [B, S, heads, D] view, element strides, D con
 
 struct Shape {
   int32_t B, Hq, Hkv, D, Sq, Sk;
-  int64_t q_offset;
+  int64_t q_offset;   // global position of query row 0
   int32_t causal;
   float scale;
+  int32_t q_seg;      // 0: one run of rows; > 0: rows [q_seg, Sq) are a second run that starts at q_offset2
+  int64_t q_offset2;  //    (two half-shards of a load-balanced causal placement); positions rise with the row
 };
+
+// Global position of query row i.
+__host__ __device__ inline int64_t q_pos(const Shape& s, int i) {
+  return (s.q_seg > 0 && i >= s.q_seg) ? s.q_offset2 + (i - s.q_seg) : s.q_offset + i;
+}
+// Smallest row index whose position is >= p: under a causal mask row i sees a key at p iff i >= q_row_of(p).
+// Sq if no row does.
+__host__ __device__ inline int q_row_of(const Shape& s, int64_t p) {
+  const int n0 = s.q_seg > 0 ? s.q_seg : s.Sq;
+  int64_t i = p - s.q_offset;
+  if (i < n0) return i < 0 ? 0 : (int)i;
+  if (s.q_seg <= 0) return s.Sq;
+  i = p - s.q_offset2;
+  if (i < 0) i = 0;
+  return i >= s.Sq - n0 ? s.Sq : n0 + (int)i;
+}
 
 // Chunks in visit order.  k/v are base pointers of [B,Sk,Hkv,D] views that share one stride set.
 struct ChunkTable {
@@ -72,12 +90,10 @@ struct CombineArgs {
 // whose rows all see the tile's last key; everything else (masked blocks, ragged tails) stays general.
 constexpr int kDkvFastKeys = 256;
 constexpr int kDkvFastRows = 32;
-__host__ __device__ inline int dkv_fast_first_block(int causal, int64_t q_offset, int64_t k0, int tile_key0) {
-  if (!causal) return 0;
-  const int64_t d = k0 + tile_key0 + kDkvFastKeys - 1 - q_offset;   // first row index that sees the last key
-  if (d <= 0) return 0;
-  const int64_t fb = (d + kDkvFastRows - 1) / kDkvFastRows;
-  return fb > 0x3fffffff ? 0x3fffffff : (int)fb;
+__host__ __device__ inline int dkv_fast_first_block(const Shape& s, int64_t k0, int tile_key0) {
+  if (!s.causal) return 0;
+  const int d = q_row_of(s, k0 + tile_key0 + kDkvFastKeys - 1);     // first row index that sees the last key
+  return (d + kDkvFastRows - 1) / kDkvFastRows;
 }
 
 // Optional per-kernel timing (st_profile_begin / st_profile_end): while enabled, a ProfScope
@@ -96,16 +112,16 @@ constexpr int kQTileFastRows = 256;
 constexpr int kQTileFastKeys = 64;
 constexpr int kDqFastRows = kQTileFastRows;
 constexpr int kDqFastKeys = kQTileFastKeys;
-__host__ __device__ inline int qtile_fast_tiles(int causal, int Sk, int64_t q_offset, int row0, int64_t k0) {
-  int64_t nv = Sk;
-  if (causal) {
-    nv = q_offset + row0 - k0 + 1;
-    nv = nv < 0 ? 0 : (nv > Sk ? Sk : nv);
+__host__ __device__ inline int qtile_fast_tiles(const Shape& s, int row0, int64_t k0) {
+  int64_t nv = s.Sk;
+  if (s.causal) {
+    nv = q_pos(s, row0) - k0 + 1;
+    nv = nv < 0 ? 0 : (nv > s.Sk ? s.Sk : nv);
   }
   return (int)(nv / kQTileFastKeys);
 }
-__host__ __device__ inline int dq_fast_tiles(int causal, int Sk, int64_t q_offset, int row0, int64_t k0) {
-  return qtile_fast_tiles(causal, Sk, q_offset, row0, k0);
+__host__ __device__ inline int dq_fast_tiles(const Shape& s, int row0, int64_t k0) {
+  return qtile_fast_tiles(s, row0, k0);
 }
 
 // ---- launchers (each returns hipGetLastError() after the launch) ----

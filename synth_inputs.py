@@ -47,6 +47,8 @@ class Workload:
     ring_C: int = 1          # team size of the concentric layout
     ring_rank: int = 0
     k_ramp: float = 0.0      # K chunk j is scaled by 1 + k_ramp * j: later chunks raise the row maxima sharply
+    q_seg: int = 0           # > 0: query rows [q_seg, Sq) are a second run of the sequence that starts at q_offset2
+    q_offset2: int = 0
 
     @property
     def scale(self) -> float:
@@ -58,6 +60,18 @@ class Workload:
 
     def k_offset(self, j: int) -> int:
         return j * self.Sk
+
+    def q_positions(self) -> np.ndarray:
+        """Global position of every query row."""
+        i = np.arange(self.Sq, dtype=np.int64)
+        if self.q_seg > 0:
+            return np.where(i < self.q_seg, self.q_offset + i, self.q_offset2 + i - self.q_seg)
+        return self.q_offset + i
+
+    @property
+    def q_where(self):
+        """The shard's placement as the binding takes it: a position, or (position, rows, position) for two runs."""
+        return (self.q_offset, self.q_seg, self.q_offset2) if self.q_seg > 0 else self.q_offset
 
 
 def paper_workloads() -> List[Workload]:
@@ -90,6 +104,16 @@ def dit_workload() -> Workload:
     shard, 8 chunks of 16384 tokens, non-causal, bf16."""
     return Workload("dit1b_full_mask_ring8", 7, "bf16", 1, 24, 24, 64, 16384, 16384, 8, 3 * 16384, False, True,
                     ring_P=8, ring_C=1, ring_rank=3)
+
+
+def zigzag_workload(rank: int = 0) -> Workload:
+    """The model of configuration 4 under the load-balanced causal placement (appendix "Sequence Parallelism
+    Dataloader"): the sequence of 131072 tokens is cut into 2 P = 64 pieces of 2048 tokens and rank r of the
+    ring of P = 32 holds pieces r and 2 P - 1 - r.  Query shard: those two pieces (4096 rows in two runs); the
+    ring delivers every rank's two pieces, here 64 chunks of 2048 tokens."""
+    P, m = 32, 2048
+    return Workload(f"zigzag32_gqa_rank{rank}", 8, "bf16", 1, 32, 8, 128, 2 * m, m, 2 * P, rank * m, True, True,
+                    ring_P=P, ring_C=1, ring_rank=rank, q_seg=m, q_offset2=(2 * P - 1 - rank) * m)
 
 
 def small_workload(name="small", dtype="bf16", B=1, Hq=2, Hkv=1, D=128, Sq=192, Sk=160,
@@ -196,7 +220,7 @@ def visible_pairs(w: Workload, chunks: Optional[Sequence[int]] = None) -> int:
     chunks = range(w.n_chunks) if chunks is None else chunks
     if not w.causal:
         return w.Sq * w.Sk * len(chunks)
-    i = np.arange(w.Sq, dtype=np.int64) + w.q_offset
+    i = w.q_positions()
     return int(sum(np.clip(i - w.k_offset(j) + 1, 0, w.Sk).sum() for j in chunks))
 
 

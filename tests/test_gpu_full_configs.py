@@ -1,5 +1,5 @@
 """GPU parity at the full benchmark sizes (configurations 3, 4 and 5, and the diffusion-transformer-shaped
-share bench.py --shape dit times), in the launch configuration bench.py times: fused ring forward, then
+share and the load-balanced placement that bench.py --shape dit / zigzag time), in the launch configuration bench.py times: fused ring forward, then
 fused ring backward, chunks visited in the ring's order.
 
 The fp64 oracle cannot do these sizes in full, so it does seeded sampled query rows of every head
@@ -23,7 +23,8 @@ pytestmark = pytest.mark.gpu
 
 # workload -> sampled rows per head (configuration 5: the 256 rows its definition names)
 CASES = {"cfg3": (lambda: si.paper_workloads()[2], 128), "cfg4": (lambda: si.paper_workloads()[3], 64),
-         "cfg5": (lambda: si.paper_workloads()[4], 256), "dit": (si.dit_workload, 64)}
+         "cfg5": (lambda: si.paper_workloads()[4], 256), "dit": (si.dit_workload, 64),
+         "zigzag": (lambda: si.zigzag_workload(5), 64)}
 
 
 @pytest.mark.timeout(900)
@@ -40,14 +41,16 @@ def test_full_size_sampled_rows(cfg):
     vs = [bits_dev(b) for b in inp.v_bits]
     koffs = [w.k_offset(j) for j in range(w.n_chunks)]
     order, members = st.st_visit_order(w.ring_P, w.ring_C, w.ring_rank)
+    if w.q_seg:     # balanced placement: the ring delivers every rank's two pieces of the sequence
+        order, members = [c for x in order for c in (x, 2 * w.ring_P - 1 - x)], None
     rows = [si.sampled_rows(w, h, n_rows) for h in range(w.Hq)]
 
     print(f"[{cfg}] GPU forward + backward, run A (dense dO)", flush=True)
-    o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, members, st.ST_RING_FUSED)
+    o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_where, koffs, w.causal, w.scale, order, members, st.ST_RING_FUSED)
     dq = torch.zeros_like(o)
     dk = [torch.zeros(k.shape, device="cuda") for k in ks]
     dv = [torch.zeros(k.shape, device="cuda") for k in ks]
-    st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq, dk, dv, st.ST_RING_FUSED)
+    st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv, st.ST_RING_FUSED)
     torch.cuda.synchronize()
     o_s = [host(o[:, torch.from_numpy(rows[h]).cuda(), h]) for h in range(w.Hq)]
     lse_s = [host(lse[:, h, torch.from_numpy(rows[h]).cuda()]) for h in range(w.Hq)]
@@ -63,7 +66,7 @@ def test_full_size_sampled_rows(cfg):
     dq_b = torch.zeros_like(o)
     dk = [torch.zeros(k.shape, device="cuda") for k in ks]
     dv = [torch.zeros(k.shape, device="cuda") for k in ks]
-    st.st_ring_bwd(q, ks, vs, d_o_b, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq_b, dk, dv,
+    st.st_ring_bwd(q, ks, vs, d_o_b, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq_b, dk, dv,
                    st.ST_RING_FUSED)
     torch.cuda.synchronize()
     assert float(torch.where(keep, torch.zeros_like(dq_b), dq_b).abs().max()) == 0.0, "dQ outside the sampled rows"
@@ -80,7 +83,7 @@ def test_full_size_sampled_rows(cfg):
         dv_ref = [np.zeros((w.B, w.Sk, 1, w.D)) for _ in range(w.n_chunks)]
         for h in range(g * G, (g + 1) * G):
             print(f"[{cfg}] oracle: head {h} ({len(rows[h])} rows x {w.N} keys)", flush=True)
-            q_pos = rows[h] + w.q_offset
+            q_pos = w.q_positions()[rows[h]]
             qh = inp.q[:, rows[h], h:h + 1, :]
             doh = inp.d_o[:, rows[h], h:h + 1, :]
             o_ref, lse_ref = oa.attention_forward(qh, kg, vg, q_pos, k_pos, w.causal, w.scale)

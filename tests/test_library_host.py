@@ -50,6 +50,13 @@ def test_team_visit_order_rejects_bad_layouts():
         assert e.value.status == 1
 
 
+def test_two_run_placements_are_validated():
+    """Second run of query rows: inside the shard, and not before the end of the first run."""
+    for bad in [dict(q_seg=8, q_offset2=100), dict(q_seg=-1, q_offset2=100), dict(q_seg=9, q_offset2=100),
+                dict(q_seg=4, q_offset2=3), dict(q_offset=10, q_seg=4, q_offset2=13)]:
+        assert _call_fwd(_desc(**bad)) == 1, bad
+
+
 def test_combine_validation_fails_before_any_launch():
     lib = api._lib
     def call(n=2, B=1, Sq_in=8, Hq=2, D=64, row0=0, Sq_out=8, o=(0x1000, 0x2000), l=(0x3000, 0x4000), out=0x5000,
@@ -74,7 +81,8 @@ def test_visit_order_rejects_bad_layouts():
 
 
 def _desc(**kw):
-    base = dict(dtype=0, B=1, Hq=2, Hkv=1, D=64, Sq=8, Sk=8, q_offset=0, k_offset=0, causal=1, scale=0.125)
+    base = dict(dtype=0, B=1, Hq=2, Hkv=1, D=64, Sq=8, Sk=8, q_offset=0, k_offset=0, causal=1, scale=0.125, q_seg=0,
+                q_offset2=0)
     base.update(kw)
     return api.st_block_desc(*[base[k] for k, _ in api.st_block_desc._fields_])
 

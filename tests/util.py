@@ -40,7 +40,7 @@ def host(t: torch.Tensor) -> np.ndarray:
 
 
 def positions(w: si.Workload):
-    q_pos = np.arange(w.Sq, dtype=np.int64) + w.q_offset
+    q_pos = w.q_positions()
     k_pos = [np.arange(w.Sk, dtype=np.int64) + w.k_offset(j) for j in range(w.n_chunks)]
     return q_pos, k_pos
 
