@@ -19,7 +19,7 @@ OBJ_DIR = os.path.join(PKG, "_build")
 SOURCES = ["st_api.cpp", "st_f32.hip", "st_elementwise.hip", "st_fwd_bf16.hip", "st_bwd_bf16.hip", "st_bwd_dkv_fast.hip", "st_bwd_dq_fast.hip", "st_fwd_fast.hip"]
 # assembly main loops written out by generator scripts before compiling: (script, output)
 GENERATED = [("gen_bwd_dkv_asm.py", "st_bwd_dkv_asm.inc"), ("gen_bwd_dq_asm.py", "st_bwd_dq_asm.inc"),
-             ("gen_fwd_asm.py", "st_fwd_asm.inc")]
+             ("gen_fwd_asm.py", "st_fwd_asm.inc"), ("gen_fwd_asm.py 64", "st_fwd64_asm.inc")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for device code on purpose (see DESIGN notes on the target)
@@ -43,7 +43,8 @@ def _compile(src: str) -> str:
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     for script, out in GENERATED:
-        r = subprocess.run([sys.executable, os.path.join(CSRC, script)], capture_output=True, text=True)
+        name, *args = script.split()
+        r = subprocess.run([sys.executable, os.path.join(CSRC, name), *args], capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"{script} failed:\n{r.stderr}")
         with open(os.path.join(CSRC, out), "w") as f:

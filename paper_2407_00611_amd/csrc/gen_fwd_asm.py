@@ -1,7 +1,9 @@
 #!/usr/bin/env python3
-"""Generates the gfx950 assembly of the forward main loop (head_dim 128) as a C string literal.
+"""Generates the gfx950 assembly of the forward main loop (head_dim 128, or 64) as a C string literal.
 
-    python gen_fwd_asm.py > st_fwd_asm.inc      (build.py does this before compiling)
+    python gen_fwd_asm.py > st_fwd_asm.inc          (build.py does this before compiling)
+    python gen_fwd_asm.py 64 > st_fwd64_asm.inc     (head_dim 64: half the contraction steps and half the
+                                                     O^T row blocks per key block, tiles of 128-byte rows)
 
 Body of ONE `asm volatile` statement in st_fwd_fast.hip.  A workgroup (4 wavefronts) owns 256 queries of
 one head, 64 per wavefront as two 32-query blocks, and walks the 64-key tiles that every one of its rows
@@ -29,12 +31,18 @@ import sys
 
 from st_asmgen import Emitter, ar, sr, vr, write_inc
 
-KS, DB, QB, NS = 8, 4, 2, 4
+D = 64 if "64" in sys.argv[1:] else 128              # head_dim
+KS, DB, QB, NS = D // 16, D // 32, 2, 4
+ROW = 2 * D                                          # bytes of one K / V row in LDS
+TILE = 64 * ROW                                      # one 64-key tile
+NDMA = TILE // 4096                                  # direct-to-LDS loads per wavefront and tile (4 wavefronts x 1 KiB each)
+NSLOT = 4 * DB + 2 * KS                              # MFMAs per key block and wavefront
+SPLIT = 4 * 2 * TILE > 65536                         # ring beyond the 16-bit offset field: second set of base registers
 GAP = 8.0                                            # log2 units a block maximum may exceed the reference by
 
 # ---- AGPRs
 def ACC(db, qb): return 16 * (2 * db + qb)
-def QF(qb, ks): return 128 + 4 * (8 * qb + ks)
+def QF(qb, ks): return 128 + 4 * (KS * qb + ks)
 
 # ---- VGPRs
 def SBUF(buf, qb): return 32 * buf + 16 * qb        # two score buffers (S, then P in fp32)
@@ -62,14 +70,14 @@ S_CEXP, T_M0, T_REM, D_KPTR, D_VPTR, D_LEFT, D_IDX, D_TBL, T_X = 47, 64, 65, 66,
 T_RET, T_RARE = 76, 78                               # return address; address of rescale routine b at 78 + 2 b
 
 # ---- LDS map
-def KT(s): return 32768 * s
-def VT(s): return 32768 * s + 16384
-TBL = 32768 * NS
+def KT(s): return 2 * TILE * s
+def VT(s): return 2 * TILE * s + TILE
+TBL = 2 * TILE * NS
 LDS_BYTES = TBL + 2048
 
 LAT = int(os.environ.get("ST_GEN_FWD_LAT", 3))
-BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 7))
-BRANCH_SLOT = 9                                      # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
+BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 7 if D == 128 else 12))
+BRANCH_SLOT = 2 * DB + 1                             # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
 
 
 class Pipe:
@@ -98,25 +106,26 @@ class Pipe:
         self.e.ds, self.frag_reg, self.uses_left, self.owner = list(snap[0]), dict(snap[1]), dict(snap[2]), dict(snap[3])
 
 
-def xreg(stage, ks): return (XL if stage < 2 else XH) + ks
-def trregs(stage): return (TRLO_L, TRHI_L) if stage < 2 else (TRLO_H, TRHI_H)
-def imm(stage, base): return base - (0 if stage < 2 else 65536)
+def upper(stage): return SPLIT and stage >= 2
+def xreg(stage, ks): return (XH if upper(stage) else XL) + ks
+def trregs(stage): return (TRLO_H, TRHI_H) if upper(stage) else (TRLO_L, TRHI_L)
+def imm(stage, base): return base - (65536 if upper(stage) else 0)
 
 
 def read_k(p, blk, ks, seq):
     stage, kb = blk
     tag = f"k{seq}_{ks}"
     r = p.alloc(0, ks, tag, QB)
-    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, KT(stage)) + 8192 * kb}", tag)
+    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, KT(stage)) + 32 * ROW * kb}", tag)
 
 
 def read_vt(p, blk, m, db, seq):
     """V^T fragment (32 d rows x 16 keys) of a block: A operand of O^T += V^T P^T."""
     stage, kb = blk
     tag = f"t{seq}_{m}_{db}"
-    r = p.alloc(1, 4 * m + db, tag, QB)
+    r = p.alloc(1, DB * m + db, tag, QB)
     lo, hi = trregs(stage)
-    off = imm(stage, VT(stage)) + 8192 * kb + 4096 * m
+    off = imm(stage, VT(stage)) + 32 * ROW * kb + 16 * ROW * m
     p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r, 2)}, {vr(lo + db)} offset:{off}", tag + "lo")
     p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(hi + db)} offset:{off}", tag)
 
@@ -173,7 +182,7 @@ def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, pr
     par = i % 2: P(i) sits in P buffer par, S(i+1) in score buffer 1 - par, S(i+2) goes to score buffer par."""
     e = p.e
     e.comment(f"======== block {cur}: O^T += V^T P^T{cur} | S^T{nxt2} -> buffer {par} | softmax of {nxt}")
-    reads = {k: [] for k in range(-1, 32)}
+    reads = {k: [] for k in range(-1, NSLOT)}
 
     def plan(first_use, fn):
         reads[max(first_use - LAT, -1)].append(fn)
@@ -181,21 +190,21 @@ def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, pr
     slots = []
     for m in range(2):
         for db in range(DB):
-            k = 2 * (4 * m + db)
+            k = 2 * (DB * m + db)
             if not (m == 0 and db < 2):                   # requested at the tail of the block before
                 plan(k, (lambda m=m, db=db: read_vt(p, cur, m, db, seq)))
             for qb in range(QB):
                 slots.append(("B", m, db, qb))
     if do_a:
         for ks in range(KS):
-            plan(16 + 2 * ks, (lambda ks=ks: read_k(p, nxt2, ks, seq)))
+            plan(4 * DB + 2 * ks, (lambda ks=ks: read_k(p, nxt2, ks, seq)))
             for qb in range(QB):
                 slots.append(("A", ks, qb))
     else:
-        slots += [None] * 16
+        slots += [None] * (2 * KS)
     if prefetch and nxt is not None:
         for db in range(2):
-            reads[29 + db].append(lambda db=db: read_vt(p, nxt, 0, db, seq + 1))
+            reads[NSLOT - 3 + db].append(lambda db=db: read_vt(p, nxt, 0, db, seq + 1))
 
     valu_m = valu_max(1 - par) if do_valu else []
     valu_e = valu_exp(1 - par, 1 - par) if do_valu else []
@@ -296,7 +305,7 @@ def gen_rescale_routine(e, pbuf):
 
 
 def gen_dma(e, stage):
-    for j in range(4):
+    for j in range(NDMA):
         e.raw(f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}")
         e.raw("s_nop 0")
         e.raw(f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}")
@@ -357,7 +366,7 @@ def generate():
     e.raw(f"v_mov_b32 {vr(VOFF)}, {vr(I_VOFF0)}")
     e.raw(f"v_mov_b32 {vr(OOFF)}, {vr(I_OOFF)}")
     e.raw(f"v_mov_b32 {vr(LSEOFF)}, {vr(I_LSEOFF)}")
-    for j in range(1, 4):
+    for j in range(1, NDMA):
         e.raw(f"v_add_u32 {vr(KOFF + j)}, {sr(S_KRS16)}, {vr(KOFF + j - 1)}")
         e.raw(f"v_add_u32 {vr(VOFF + j)}, {sr(S_VRS16)}, {vr(VOFF + j - 1)}")
     gen_table_entry(e)
@@ -366,27 +375,29 @@ def generate():
     e.comment("Q fragments (B operands) -> AGPRs; lane = query column, elements 16 ks + 8 (lane / 32) .. + 7")
     for qb, qrow in enumerate((I_QROW0, I_QROW1)):
         for ks in range(KS):
-            e.raw(f"global_load_dwordx4 {vr(4 * (8 * qb + ks), 4)}, {vr(qrow, 2)}, off offset:{32 * ks}")
+            e.raw(f"global_load_dwordx4 {vr(4 * (KS * qb + ks), 4)}, {vr(qrow, 2)}, off offset:{32 * ks}")
     for ks in range(KS):
         e.raw(f"v_xor_b32 {vr(TMP)}, {32 * ks}, {vr(I_GF16)}")
         e.raw(f"v_add_u32 {vr(XL + ks)}, {vr(I_XBASE)}, {vr(TMP)}")
-        e.raw(f"v_add_u32 {vr(XH + ks)}, 0x10000, {vr(XL + ks)}")
+        if SPLIT:
+            e.raw(f"v_add_u32 {vr(XH + ks)}, 0x10000, {vr(XL + ks)}")
     for db in range(DB):
         e.raw(f"v_xor_b32 {vr(TMP)}, {64 * db}, {vr(I_LF16)}")
         e.raw(f"v_add_u32 {vr(TRLO_L + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
         e.raw(f"v_xor_b32 {vr(TMP)}, {(64 * db) ^ 32}, {vr(I_LF16)}")
         e.raw(f"v_add_u32 {vr(TRHI_L + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
-        e.raw(f"v_add_u32 {vr(TRHI_L + db)}, 2048, {vr(TRHI_L + db)}")
-        e.raw(f"v_add_u32 {vr(TRLO_H + db)}, 0x10000, {vr(TRLO_L + db)}")
-        e.raw(f"v_add_u32 {vr(TRHI_H + db)}, 0x10000, {vr(TRHI_L + db)}")
-    for i in range(128):
+        e.raw(f"v_add_u32 {vr(TRHI_L + db)}, {8 * ROW}, {vr(TRHI_L + db)}")
+        if SPLIT:
+            e.raw(f"v_add_u32 {vr(TRLO_H + db)}, 0x10000, {vr(TRLO_L + db)}")
+            e.raw(f"v_add_u32 {vr(TRHI_H + db)}, 0x10000, {vr(TRHI_L + db)}")
+    for i in range(32 * DB):
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
     for qb in range(QB):
         for m in range(2):
             e.raw(f"v_mov_b32 {vr(LSUM(qb, m))}, 0")
     e.raw("s_waitcnt vmcnt(0)")
     e.comment("Q <- bf16(Q * scale * log2(e)): the MFMAs then deliver exponents in log2 units")
-    for i in range(0, 64, 4):
+    for i in range(0, 8 * KS, 4):
         for j in range(4):
             e.raw(f"v_lshlrev_b32 {vr(64 + 2 * j)}, 16, {vr(i + j)}")
             e.raw(f"v_and_b32 {vr(65 + 2 * j)}, 0xffff0000, {vr(i + j)}")
@@ -394,7 +405,7 @@ def generate():
             e.raw(f"v_mul_f32 {vr(64 + j)}, {sr(S_CEXP)}, {vr(64 + j)}")
         for j in range(4):
             e.raw(f"v_cvt_pk_bf16_f32 {vr(i + j)}, {vr(64 + 2 * j)}, {vr(65 + 2 * j)}")
-    for i in range(64):
+    for i in range(8 * KS):
         e.raw(f"v_accvgpr_write_b32 {ar(128 + i)}, {vr(i)}")
     e.raw("s_barrier")
 
@@ -442,7 +453,7 @@ def generate():
 
         def head(u=u):
             # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: request tile T + 3
-            e.raw("s_waitcnt vmcnt(8)")
+            e.raw(f"s_waitcnt vmcnt({2 * NDMA})")
             e.raw("s_barrier")
             gen_dma(e, (u + 3) % NS)
         leftover += gen_iter(p, (u, 0), (u, 1), (un, 0), 0, seq, head=head)
@@ -508,7 +519,8 @@ def main():
         sys.stderr.write(f"gen_fwd_asm: {leftover} VALU instructions did not fit under the MFMAs\n")
     clob = [f"v{i}" for i in range(256) if not 224 <= i < 240] + [f"a{i}" for i in range(256)]
     clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 82)]
-    write_inc(sys.stdout, "gen_fwd_asm.py", "ST_FWD_FAST", e, LDS_BYTES, clob)
+    write_inc(sys.stdout, "gen_fwd_asm.py" + (" 64" if D == 64 else ""), "ST_FWD_FAST" + ("64" if D == 64 else ""), e,
+              LDS_BYTES, clob)
 
 
 if __name__ == "__main__":

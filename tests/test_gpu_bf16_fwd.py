@@ -24,6 +24,12 @@ STEP_CASES = [
     ("fast_two_tiles", 1, 1, 1, 128, 256, 128, 1, 0, False),
     ("fast_chunk_switches", 2, 4, 2, 128, 300, 320, 3, 0, False),
     ("fast_causal_mix", 1, 2, 1, 128, 512, 200, 5, 520, True),
+    # the same loop generated for head size 64
+    ("fast64_one_tile", 1, 1, 1, 64, 256, 64, 1, 0, False),
+    ("fast64_two_tiles", 1, 1, 1, 64, 256, 128, 1, 0, False),
+    ("fast64_chunk_switches", 2, 4, 2, 64, 300, 320, 3, 0, False),
+    ("fast64_causal_mix", 1, 2, 1, 64, 512, 200, 5, 520, True),
+    ("fast64_long", 1, 3, 3, 64, 256, 1024, 3, 0, False),
 ]
 
 
@@ -32,10 +38,11 @@ def _workload(c):
     return si.Workload(name, 80 + len(name), "bf16", B, Hq, Hkv, D, Sq, Sk, n, q0, causal, False)
 
 
-def test_ring_forward_rising_maxima():
+@pytest.mark.parametrize("D", [128, 64])
+def test_ring_forward_rising_maxima(D):
     """Keys grow from chunk to chunk, so the row maxima jump by far more than the lazy reference tolerates:
     the rescale routine of the hand-scheduled loop runs several times per row."""
-    w = si.Workload("fast_rescale", 86, "bf16", 1, 2, 1, 128, 256, 192, 5, 5 * 192 - 256, True, False, k_ramp=1.0)
+    w = si.Workload("fast_rescale", 86, "bf16", 1, 2, 1, D, 256, 192, 5, 5 * 192 - 256, True, False, k_ramp=1.0)
     inp = si.make_inputs(w)
     q, ks, vs, _ = upload(inp)
     q_pos, k_pos = positions(w)
