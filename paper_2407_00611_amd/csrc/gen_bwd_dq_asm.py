@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
-"""Generates the gfx950 assembly of the dQ main loop (head_dim 128) as a C string literal.
+"""Generates the gfx950 assembly of the dQ main loop (head_dim 128, or 64) as a C string literal.
 
-    python gen_bwd_dq_asm.py > st_bwd_dq_asm.inc      (build.py does this before compiling)
+    python gen_bwd_dq_asm.py > st_bwd_dq_asm.inc          (build.py does this before compiling)
+    python gen_bwd_dq_asm.py 64 > st_bwd_dq64_asm.inc     (head_dim 64: half the MFMAs per group, 128-byte tile rows)
 
 Body of ONE `asm volatile` statement in st_bwd_dq_fast.hip.  A workgroup (4 wavefronts) owns 256 queries
 of one head, 64 per wavefront as two 32-query blocks, and walks the 64-key tiles that every one of its
@@ -25,12 +26,19 @@ import sys
 
 from st_asmgen import Emitter, ar, sr, vr, write_inc
 
-KS, DB, QB, NS = 8, 4, 2, 4
+D = 64 if "64" in sys.argv[1:] else 128              # head_dim
+KS, DB, QB, NS = D // 16, D // 32, 2, 4
+ROW = 2 * D                                          # bytes of one K / V row in LDS
+TILE = 64 * ROW                                      # one 64-key tile
+NDMA = TILE // 4096                                  # direct-to-LDS loads per wavefront and tile (4 wavefronts x 1 KiB each)
+NA, NB, NC = 2 * KS, 4 * DB, 2 * KS                  # MFMAs of the three groups of a key block
+NSLOT = NA + NB + NC
+SPLIT = 4 * 2 * TILE > 65536                         # ring beyond the 16-bit offset field: second set of base registers
 
 # ---- AGPRs
 def ACC(db, qb): return 16 * (2 * db + qb)
-def QF(qb, ks): return 128 + 4 * (8 * qb + ks)
-def DOF(qb, ks): return 192 + 4 * (8 * qb + ks)
+def QF(qb, ks): return 128 + 4 * (KS * qb + ks)
+def DOF(qb, ks): return 192 + 4 * (KS * qb + ks)
 
 # ---- VGPRs
 def SBUF(buf, qb): return 32 * buf + 16 * qb        # two score buffers (later P, fp32)
@@ -54,13 +62,13 @@ PT = 184                                             # 184..199: temporaries of 
 S_CEXP, T_M0, T_REM, D_KPTR, D_VPTR, D_LEFT, D_IDX, D_TBL, T_X = 47, 64, 65, 66, 68, 70, 71, 72, 73
 
 # ---- LDS map
-def KT(s): return 32768 * s
-def VT(s): return 32768 * s + 16384
-TBL = 32768 * NS                                     # 64 entries x 32 bytes: k lo/hi, v lo/hi, tiles, pad
+def KT(s): return 2 * TILE * s
+def VT(s): return 2 * TILE * s + TILE
+TBL = 2 * TILE * NS                                     # 64 entries x 32 bytes: k lo/hi, v lo/hi, tiles, pad
 LDS_BYTES = TBL + 2048
 
 LAT = int(os.environ.get("ST_GEN_DQ_LAT", 3))
-BUDGET = int(os.environ.get("ST_GEN_DQ_BUDGET", 6))
+BUDGET = int(os.environ.get("ST_GEN_DQ_BUDGET", 6 if D == 128 else 8))
 
 
 class Pipe:
@@ -89,30 +97,31 @@ class Pipe:
         return self.frag_reg[tag]
 
 
-def xreg(stage, ks): return (XL if stage < 2 else XH) + ks
-def trregs(stage, db): return ((TRLO_L, TRHI_L) if stage < 2 else (TRLO_H, TRHI_H))
-def imm(stage, tensor_base): return tensor_base - (0 if stage < 2 else 65536)
+def upper(stage): return SPLIT and stage >= 2
+def xreg(stage, ks): return (XH if upper(stage) else XL) + ks
+def trregs(stage, db): return ((TRLO_H, TRHI_H) if upper(stage) else (TRLO_L, TRHI_L))
+def imm(stage, tensor_base): return tensor_base - (65536 if upper(stage) else 0)
 
 
 def read_k(p, stage, kb, ks, seq):
     """K rows of block (stage, kb), contraction step ks: A operand of S^T."""
     tag = f"k{seq}_{ks}"
     r = p.alloc(0, ks, tag, QB)
-    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, KT(stage)) + 8192 * kb}", tag)
+    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, KT(stage)) + 32 * ROW * kb}", tag)
 
 
 def read_v(p, stage, kb, ks, seq):
     tag = f"v{seq}_{ks}"
     r = p.alloc(2, ks, tag, QB)
-    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, VT(stage)) + 8192 * kb}", tag)
+    p.e.ds_read(f"ds_read_b128 {vr(r, 4)}, {vr(xreg(stage, ks))} offset:{imm(stage, VT(stage)) + 32 * ROW * kb}", tag)
 
 
 def read_kt(p, stage, kb, m, db, seq):
     """K^T fragment (32 d rows x 16 keys) of block (stage, kb): A operand of dQ^T."""
     tag = f"t{seq}_{m}_{db}"
-    r = p.alloc(1, 4 * m + db, tag, QB)
+    r = p.alloc(1, DB * m + db, tag, QB)
     lo, hi = trregs(stage, db)
-    off = imm(stage, KT(stage)) + 8192 * kb + 4096 * m
+    off = imm(stage, KT(stage)) + 32 * ROW * kb + 16 * ROW * m
     p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r, 2)}, {vr(lo + db)} offset:{off}", tag + "lo")
     p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(hi + db)} offset:{off}", tag)
 
@@ -126,7 +135,7 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
     nbuf = 1 - pbuf
     e.comment(f"======== block {cur}: S^T{nxt} -> buffer {nbuf} | dQ^T += K^T dS^T{cur} | dP'^T{nxt}")
     slots = []
-    reads = {k: [] for k in range(-1, 48)}
+    reads = {k: [] for k in range(-1, NSLOT)}
 
     def plan(first_use, fn):
         reads[max(first_use - LAT, -1)].append(fn)
@@ -138,25 +147,25 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
             for qb in range(QB):
                 slots.append(("A", ks, qb))
     else:
-        slots += [None] * 16
+        slots += [None] * NA
     if do_b:
         for m in range(2):
             for db in range(DB):
-                plan(16 + 2 * (4 * m + db), (lambda m=m, db=db: read_kt(p, cur[0], cur[1], m, db, seq)))
+                plan(NA + 2 * (DB * m + db), (lambda m=m, db=db: read_kt(p, cur[0], cur[1], m, db, seq)))
                 for qb in range(QB):
                     slots.append(("B", m, db, qb))
     else:
-        slots += [None] * 16
+        slots += [None] * NB
     if do_ac:
         for ks in range(KS):
-            plan(32 + 2 * ks, (lambda ks=ks: read_v(p, nxt[0], nxt[1], ks, seq)))
+            plan(NA + NB + 2 * ks, (lambda ks=ks: read_v(p, nxt[0], nxt[1], ks, seq)))
             for qb in range(QB):
                 slots.append(("C", ks, qb))
         if nxt2 is not None:
             for ks in range(2):
-                reads[44 + ks].append(lambda ks=ks: read_k(p, nxt2[0], nxt2[1], ks, seq + 1))
+                reads[NSLOT - 4 + ks].append(lambda ks=ks: read_k(p, nxt2[0], nxt2[1], ks, seq + 1))
     else:
-        slots += [None] * 16
+        slots += [None] * NC
 
     # ---- VALU work: (earliest slot, text, registers written, issue units)
     valu = []
@@ -169,8 +178,8 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
                     d, a = DP(qb) + 4 * m + i, DP(qb) + 8 * m + 2 * i
                     valu.append((2 + qb, f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1))
     # the first VALU reader of an MFMA result comes three MFMA issues after the MFMA
-    early1 = 17 if do_b else 34
-    if do_ac:  # P(i+1) = exp2(exponent); S^T(i+1)[qb] is written by slot 14 + qb
+    early1 = NA + 1 if do_b else NA + NB + 2
+    if do_ac:  # P(i+1) = exp2(exponent); S^T(i+1)[qb] is written by slot NA - 2 + qb
         for qb in range(QB):
             for grp in range(4):
                 vs = [SBUF(nbuf, qb) + 4 * grp + i for i in range(4)]
@@ -232,7 +241,7 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
 
 
 def gen_dma(e, stage):
-    for j in range(4):
+    for j in range(NDMA):
         e.raw(f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}")
         e.raw("s_nop 0")
         e.raw(f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}")
@@ -286,7 +295,7 @@ def generate():
     e.raw(f"v_mov_b32 {vr(KOFF)}, {vr(I_KOFF0)}")
     e.raw(f"v_mov_b32 {vr(VOFF)}, {vr(I_VOFF0)}")
     e.raw(f"v_mov_b32 {vr(DQOFF)}, {vr(I_DQOFF)}")
-    for j in range(1, 4):
+    for j in range(1, NDMA):
         e.raw(f"v_add_u32 {vr(KOFF + j)}, {sr(S_KRS16)}, {vr(KOFF + j - 1)}")
         e.raw(f"v_add_u32 {vr(VOFF + j)}, {sr(S_VRS16)}, {vr(VOFF + j - 1)}")
     gen_table_entry(e)
@@ -295,26 +304,28 @@ def generate():
     e.comment("Q / dO fragments (B operands) -> AGPRs; lane = query column, elements 16 ks + 8 (lane / 32) .. + 7")
     for qb, (qrow, dorow) in enumerate(((I_QROW0, I_DOROW0), (I_QROW1, I_DOROW1))):
         for ks in range(KS):
-            e.raw(f"global_load_dwordx4 {vr(4 * (8 * qb + ks), 4)}, {vr(qrow, 2)}, off offset:{32 * ks}")
-            e.raw(f"global_load_dwordx4 {vr(64 + 4 * (8 * qb + ks), 4)}, {vr(dorow, 2)}, off offset:{32 * ks}")
+            e.raw(f"global_load_dwordx4 {vr(4 * (KS * qb + ks), 4)}, {vr(qrow, 2)}, off offset:{32 * ks}")
+            e.raw(f"global_load_dwordx4 {vr(64 + 4 * (KS * qb + ks), 4)}, {vr(dorow, 2)}, off offset:{32 * ks}")
     e.comment("LDS offsets: x[ks] = xbase + (gf16 ^ 32 ks); transpose reads: trbase + (lf16 ^ 64 db), second half 8 rows down")
     for ks in range(KS):
         e.raw(f"v_xor_b32 {vr(TMP)}, {32 * ks}, {vr(I_GF16)}")
         e.raw(f"v_add_u32 {vr(XL + ks)}, {vr(I_XBASE)}, {vr(TMP)}")
-        e.raw(f"v_add_u32 {vr(XH + ks)}, 0x10000, {vr(XL + ks)}")
+        if SPLIT:
+            e.raw(f"v_add_u32 {vr(XH + ks)}, 0x10000, {vr(XL + ks)}")
     for db in range(DB):
         e.raw(f"v_xor_b32 {vr(TMP)}, {64 * db}, {vr(I_LF16)}")
         e.raw(f"v_add_u32 {vr(TRLO_L + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
         e.raw(f"v_xor_b32 {vr(TMP)}, {(64 * db) ^ 32}, {vr(I_LF16)}")
         e.raw(f"v_add_u32 {vr(TRHI_L + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
-        e.raw(f"v_add_u32 {vr(TRHI_L + db)}, 2048, {vr(TRHI_L + db)}")
-        e.raw(f"v_add_u32 {vr(TRLO_H + db)}, 0x10000, {vr(TRLO_L + db)}")
-        e.raw(f"v_add_u32 {vr(TRHI_H + db)}, 0x10000, {vr(TRHI_L + db)}")
-    for i in range(128):
+        e.raw(f"v_add_u32 {vr(TRHI_L + db)}, {8 * ROW}, {vr(TRHI_L + db)}")
+        if SPLIT:
+            e.raw(f"v_add_u32 {vr(TRLO_H + db)}, 0x10000, {vr(TRLO_L + db)}")
+            e.raw(f"v_add_u32 {vr(TRHI_H + db)}, 0x10000, {vr(TRHI_L + db)}")
+    for i in range(32 * DB):
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
     e.raw("s_waitcnt vmcnt(0)")
     e.comment("Q <- bf16(Q * scale * log2(e)): the S^T MFMAs then deliver exponents in log2 units")
-    for i in range(0, 64, 4):
+    for i in range(0, 8 * KS, 4):
         for j in range(4):
             e.raw(f"v_lshlrev_b32 {vr(PT + 2 * j)}, 16, {vr(i + j)}")
             e.raw(f"v_and_b32 {vr(PT + 1 + 2 * j)}, 0xffff0000, {vr(i + j)}")
@@ -322,7 +333,7 @@ def generate():
             e.raw(f"v_mul_f32 {vr(PT + j)}, {sr(S_CEXP)}, {vr(PT + j)}")
         for j in range(4):
             e.raw(f"v_cvt_pk_bf16_f32 {vr(i + j)}, {vr(PT + 2 * j)}, {vr(PT + 1 + 2 * j)}")
-    for i in range(64):
+    for i in range(8 * KS):
         e.raw(f"v_accvgpr_write_b32 {ar(128 + i)}, {vr(i)}")
         e.raw(f"v_accvgpr_write_b32 {ar(192 + i)}, {vr(64 + i)}")
     for qb, src in ((0, I_ND0), (1, I_ND1)):
@@ -345,7 +356,7 @@ def generate():
 
         def head(u=u):
             # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: request tile T + 3
-            e.raw("s_waitcnt vmcnt(8)")
+            e.raw(f"s_waitcnt vmcnt({2 * NDMA})")
             e.raw("s_barrier")
             gen_dma(e, (u + 3) % NS)
         # the head sits between the tail prefetch of the block before and this block's first MFMA
@@ -383,7 +394,7 @@ def generate():
         for db in range(DB):
             for j in range(4):
                 t = 4 * (4 * db + j)
-                e.raw(f"s_waitcnt vmcnt({15 - (4 * db + j)})")
+                e.raw(f"s_waitcnt vmcnt({4 * DB - 1 - (4 * db + j)})")
                 for i in range(4):
                     e.raw(f"v_accvgpr_read_b32 {vr(TMP)}, {ar(ACC(db, qb) + 4 * j + i)}")
                     e.raw("s_nop 0")
@@ -399,7 +410,8 @@ def main():
     e = generate()
     clob = [f"v{i}" for i in range(256) if not 160 <= i < 180] + [f"a{i}" for i in range(256)]
     clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 76)]
-    write_inc(sys.stdout, "gen_bwd_dq_asm.py", "ST_DQ_FAST", e, LDS_BYTES, clob)
+    write_inc(sys.stdout, "gen_bwd_dq_asm.py" + (" 64" if D == 64 else ""), "ST_DQ_FAST" + ("64" if D == 64 else ""), e,
+              LDS_BYTES, clob)
 
 
 if __name__ == "__main__":

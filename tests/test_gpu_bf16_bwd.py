@@ -30,6 +30,16 @@ STEP_CASES = [
     ("dq_fast_two_tiles", 1, 1, 1, 128, 256, 128, 1, 0, False),
     ("dq_fast_chunk_switches", 2, 4, 2, 128, 300, 320, 3, 0, False),
     ("dq_fast_causal_mix", 1, 2, 1, 128, 512, 200, 5, 520, True),
+    # the same loops generated for head size 64
+    ("dq_fast64_one_tile", 1, 1, 1, 64, 256, 64, 1, 0, False),
+    ("dq_fast64_two_tiles", 1, 1, 1, 64, 256, 128, 1, 0, False),
+    ("dq_fast64_chunk_switches", 2, 4, 2, 64, 300, 320, 3, 0, False),
+    ("dq_fast64_causal_mix", 1, 2, 1, 64, 512, 200, 5, 520, True),
+    ("dq_fast64_long", 1, 3, 3, 64, 256, 1024, 3, 0, False),
+    ("fast64_one_block", 1, 2, 2, 64, 32, 256, 1, 0, False),
+    ("fast64_gqa_two_tiles", 2, 4, 2, 64, 160, 512, 2, 700, True),
+    ("fast64_three_heads_ragged", 1, 3, 1, 64, 103, 296, 2, 1000, True),
+    ("fast64_long_run", 1, 2, 1, 64, 416, 256, 2, 256, True),
 ]
 
 
