@@ -20,7 +20,7 @@ SOURCES = ["st_api.cpp", "st_f32.hip", "st_elementwise.hip", "st_fwd_bf16.hip", 
 # assembly main loops written out by generator scripts before compiling: (script, output)
 GENERATED = [("gen_bwd_dkv_asm.py", "st_bwd_dkv_asm.inc"), ("gen_bwd_dq_asm.py", "st_bwd_dq_asm.inc"),
              ("gen_fwd_asm.py", "st_fwd_asm.inc"), ("gen_fwd_asm.py 64", "st_fwd64_asm.inc"),
-             ("gen_bwd_dq_asm.py 64", "st_bwd_dq64_asm.inc")]
+             ("gen_bwd_dq_asm.py 64", "st_bwd_dq64_asm.inc"), ("gen_bwd_dkv_asm.py 64", "st_bwd_dkv64_asm.inc")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for device code on purpose (see DESIGN notes on the target)

@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
-"""Generates the gfx950 assembly of the dK/dV main loop (head_dim 128) as a C string literal.
+"""Generates the gfx950 assembly of the dK/dV main loop (head_dim 128, or 64) as a C string literal.
 
-    python gen_bwd_dkv_asm.py > st_bwd_dkv_asm.inc      (build.py does this before compiling)
+    python gen_bwd_dkv_asm.py > st_bwd_dkv_asm.inc          (build.py does this before compiling)
+    python gen_bwd_dkv_asm.py 64 > st_bwd_dkv64_asm.inc     (head_dim 64: half the MFMAs per phase, 128-byte tile rows)
 
 The text is the body of ONE `asm volatile` statement in st_bwd_dkv_fast.hip.  The C++ kernel around it
 computes addresses and hands them over in pinned registers (see IN_V / IN_S below); everything between
@@ -36,13 +37,20 @@ from st_asmgen import Emitter, ar, sr, vr, write_inc
 # ------------------------------------------------------------------------------------------------
 # register map
 # ------------------------------------------------------------------------------------------------
+D = 64 if "64" in sys.argv[1:] else 128    # head_dim
 NKB = 2          # 32-key blocks per wavefront
-KS = 8           # contraction steps over head_dim (16 each)
-DB = 4           # 32-row blocks of head_dim
+KS = D // 16     # contraction steps over head_dim (16 each)
+DB = D // 32     # 32-row blocks of head_dim
 NS = 4           # LDS stages of the Q / dO ring
 PF = 3           # tiles in flight ahead of the one being computed
+ROW = 2 * D      # bytes of one tile row in LDS
+TQ = 32 * ROW    # one 32-query Q (or dO) tile
+NDQ = TQ // 4096 # direct-to-LDS loads per wavefront and tile (4 wavefronts x 1 KiB each)
+NREQ = 2 + 2 * NDQ                                   # memory operations of one block's request
+P1, P2, P3, P4 = 0, 2 * KS, 4 * KS, 4 * KS + 4 * DB  # first MFMA slot of the four phases
+NSLOT = 4 * KS + 8 * DB                              # MFMAs per block and wavefront
 
-def KF(nb, ks): return 4 * (8 * nb + ks)            # v[KF : KF+3]
+def KF(nb, ks): return 4 * (KS * nb + ks)            # v[KF : KF+3]
 S0 = 64                                              # S[nb][v]  = v[64 + 16 nb + v]   (later P, fp32)
 DP0 = 96                                             # dP[nb][v] = v[96 + 16 nb + v]   (later dS, then packed dS)
 P16 = 128                                            # P16[nb][m] = v[128 + 8 nb + 4 m : +3]
@@ -77,13 +85,13 @@ def ACC_V(db, nb): return 128 + 16 * (2 * db + nb)
 
 # LDS map (bytes, relative to the kernel's LDS base)
 STATS = 0                                            # stage s: nl[32] at 256 s, nd[32] at 256 s + 128
-def QT(s): return 1024 + 16384 * s
-def DOT(s): return 1024 + 16384 * s + 8192
-VT = 1024 + 16384 * NS                               # 256 x 128 bf16 V tile (64 KiB)
-LDS_BYTES = VT + 65536
+def QT(s): return 1024 + 2 * TQ * s
+def DOT(s): return 1024 + 2 * TQ * s + TQ
+VT = 1024 + 2 * TQ * NS                              # V tile of the workgroup: 256 rows
+LDS_BYTES = VT + 256 * ROW
 
 LAT = int(os.environ.get("ST_GEN_DKV_LAT", 3))          # MFMA slots between the issue of an LDS read and its first use
-BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6))       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
+BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6 if D == 128 else 9))       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
 
 
 
@@ -119,7 +127,7 @@ def request_code(stage, st_set):
     c = [[f"global_load_dword {vr(ST + 2 * st_set)}, {vr(STAT_G)}, {sr(T_LSEPTR, 2)}",
           f"global_load_dword {vr(ST + 2 * st_set + 1)}, {vr(STAT_G)}, {sr(T_DLPTR, 2)}"]]
     for ptr, off, tbase in ((T_QPTR, QOFF, QT(stage)), (T_DOPTR, DOOFF, DOT(stage))):
-        for j in range(2):
+        for j in range(NDQ):
             c.append([f"s_add_u32 m0, {sr(T_M0)}, {tbase + 4096 * j}", "s_nop 0",
                       f"global_load_lds_dwordx4 {vr(off + j)}, {sr(ptr, 2)}"])
     return c
@@ -161,7 +169,7 @@ def plan_reads(e, pool, u, seq):
     """LDS reads of the block on stage u, by the MFMA slot behind which they are issued; negative slots are
     issued by the block before (slot + 64) or by the prologue."""
     qt, dot_, stats = QT(u), DOT(u), STATS + 256 * u
-    reads = {k: [] for k in range(-LAT, 64)}
+    reads = {k: [] for k in range(-LAT, NSLOT)}
 
     def plan(first_use, fn):
         reads[first_use - LAT].append(fn)
@@ -175,8 +183,8 @@ def plan_reads(e, pool, u, seq):
     def rd_tr(tag, tile_imm, m, db):
         def f():
             r = pool.alloc(tag, NKB)
-            e.ds_read(f"ds_read_b64_tr_b16 {vr(r, 2)}, {vr(TRLO + db)} offset:{tile_imm + 4096 * m}", tag + "lo")
-            e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(TRHI + db)} offset:{tile_imm + 4096 * m}", tag)
+            e.ds_read(f"ds_read_b64_tr_b16 {vr(r, 2)}, {vr(TRLO + db)} offset:{tile_imm + 16 * ROW * m}", tag + "lo")
+            e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(TRHI + db)} offset:{tile_imm + 16 * ROW * m}", tag)
         return f
 
     def rd_stat(tag, base_reg, imm):
@@ -191,20 +199,20 @@ def plan_reads(e, pool, u, seq):
             plan(0, rd_stat(f"{seq}nl", NL, stats))
             plan(1, rd_stat(f"{seq}nd", ND, stats + 128))
     for ks in range(KS):
-        base = 16 + 2 * ks
+        base = P2 + 2 * ks
         plan(base, rd_nat(f"{seq}do{ks}", dot_, ks, X, NKB))
         for nb in range(NKB):
-            plan(base + nb, rd_nat(f"{seq}v{nb}_{ks}", 8192 * nb, ks, XV, 1))
+            plan(base + nb, rd_nat(f"{seq}v{nb}_{ks}", 32 * ROW * nb, ks, XV, 1))
     for ph, tile in (("dV", dot_), ("dK", qt)):
         for m in range(2):
             for db in range(DB):
-                base = (32 if ph == "dV" else 48) + 2 * (4 * m + db)
+                base = (P3 if ph == "dV" else P4) + 2 * (DB * m + db)
                 plan(base, rd_tr(f"{seq}{ph}t{m}_{db}", tile, m, db))
     return reads
 
 
-SYNC_SLOT = 31            # the barrier sits behind this MFMA slot (end of phase 2)
-PUBLISH_SLOT = 26         # wait for the next block's loads and write its statistics behind this slot
+SYNC_SLOT = P3 - 1        # the barrier sits behind this MFMA slot (end of phase 2)
+PUBLISH_SLOT = P3 - 6     # wait for the next block's loads and write its statistics behind this slot
 
 
 def gen_step(e, pool, u, seq, reads, next_reads):
@@ -227,10 +235,10 @@ def gen_step(e, pool, u, seq, reads, next_reads):
     valu = []
     def S(nb, v): return S0 + 16 * nb + v
     def DP(nb, v): return DP0 + 16 * nb + v
-    # VALU-1: P = exp2(E); pack P.  S[nb] is written by slot 14 + nb; its first reader comes three MFMA issues later.
+    # VALU-1: P = exp2(E); pack P.  S[nb] is written by slot P2 - 2 + nb; its first reader comes three MFMA issues later.
     for m in range(2):
         for nb in range(NKB):
-            early = 17 + nb
+            early = P2 + 1 + nb
             for grp in range(2):
                 vs = [8 * m + 4 * grp + i for i in range(4)]
                 for v in vs:
@@ -239,11 +247,11 @@ def gen_step(e, pool, u, seq, reads, next_reads):
                     for i in range(4):
                         d = P16 + 8 * nb + 4 * m + i
                         a = S(nb, 8 * m + 2 * i)
-                        valu.append((max(early, 20), f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1, None))
-    # VALU-2: dS = P dP', packed in place.  dP[nb] is written by slot 30 + nb; same distance.
+                        valu.append((max(early, P2 + 4), f"v_cvt_pk_bf16_f32 {vr(d)}, {vr(a)}, {vr(a + 1)}", (d,), 1, None))
+    # VALU-2: dS = P dP', packed in place.  dP[nb] is written by slot P3 - 2 + nb; same distance.
     for m in range(2):
         for nb in range(NKB):
-            early = 33 + nb
+            early = P3 + 1 + nb
             for v in range(8 * m, 8 * m + 8):
                 valu.append((early, f"v_mul_f32 {vr(DP(nb, v))}, {vr(S(nb, v))}, {vr(DP(nb, v))}", (), 1, None))
             for i in range(4):
@@ -271,15 +279,15 @@ def gen_step(e, pool, u, seq, reads, next_reads):
             vi[0] += 1
 
     # scalar / memory side work behind fixed slots
-    side = {k: [] for k in range(64)}
+    side = {k: [] for k in range(NSLOT)}
     req = request_code((u + PF) % NS, (u + 1) % 2)
     for i, grp in enumerate(req):                       # behind the barrier, one memory operation group per slot
         side[SYNC_SLOT + 1 + i] += grp
     adv = advance_code()
-    per = 4
+    per = 4 if D == 128 else 8
     for i in range(0, len(adv), per):                   # under phase 4, where the VALU is idle
-        side[48 + i // per] += adv[i:i + per]
-    assert 48 + (len(adv) - 1) // per < 61
+        side[P4 + i // per] += adv[i:i + per]
+    assert P4 + (len(adv) - 1) // per < NSLOT - 3
 
     stw = f"{seq}stw"
     for k, sl in enumerate(slots):
@@ -318,7 +326,7 @@ def gen_step(e, pool, u, seq, reads, next_reads):
             e.mfma(ar(acc, 16), vr(pool.use(tag), 4), vr(b0, 4), ar(acc, 16), breads=[b0 + i for i in range(4)])
         # ---- side work of this slot
         units = 0
-        for fn in reads[k] + (next_reads[k - 64] if k - 64 in next_reads else []):
+        for fn in reads[k] + (next_reads[k - NSLOT] if k - NSLOT in next_reads else []):
             n0 = len(e.ds)
             fn()
             units += len(e.ds) - n0
@@ -327,7 +335,7 @@ def gen_step(e, pool, u, seq, reads, next_reads):
             units += 1
         if k == PUBLISH_SLOT:
             # tile and statistics of the next block: everything but the six newest memory operations has landed
-            e.raw("s_waitcnt vmcnt(6)")
+            e.raw(f"s_waitcnt vmcnt({NREQ})")
             stat_publish(e, (u + 1) % 2, (u + 1) % NS, stw)
             units += 8
         while vi[0] < len(valu) and valu[vi[0]][0] <= k and units + valu[vi[0]][3] <= BUDGET:
@@ -364,18 +372,19 @@ def generate():
         for ks in range(KS):
             e.raw(f"global_load_dwordx4 {vr(KF(nb, ks), 4)}, {vr(krow, 2)}, off offset:{32 * ks}")
     e.comment("---- V tile of the workgroup (256 rows) to LDS: instruction 4 j + wave covers rows 16 j + 4 wave .. + 3")
-    for j in range(16):
+    for j in range(256 * ROW // 4096):
         e.raw(f"s_add_u32 m0, {sr(T_M0)}, {VT + 4096 * j}")
         e.raw("s_nop 0")
         e.raw(f"global_load_lds_dwordx4 {vr(I_VOFF)}, {sr(T_VPTR, 2)}")
-        if j < 15:
+        if j < 256 * ROW // 4096 - 1:
             e.raw(f"s_add_u32 {sr(T_VPTR)}, {sr(T_VPTR)}, {sr(S_VRS16)}")
             e.raw(f"s_addc_u32 {sr(T_VPTR + 1)}, {sr(T_VPTR + 1)}, 0")
     e.comment("---- per-lane address registers")
     e.raw(f"v_mov_b32 {vr(QOFF)}, {vr(I_QOFF0)}")
-    e.raw(f"v_mov_b32 {vr(QOFF + 1)}, {vr(I_QOFF1)}")
     e.raw(f"v_mov_b32 {vr(DOOFF)}, {vr(I_DOOFF0)}")
-    e.raw(f"v_mov_b32 {vr(DOOFF + 1)}, {vr(I_DOOFF1)}")
+    if NDQ == 2:
+        e.raw(f"v_mov_b32 {vr(QOFF + 1)}, {vr(I_QOFF1)}")
+        e.raw(f"v_mov_b32 {vr(DOOFF + 1)}, {vr(I_DOOFF1)}")
     e.raw(f"v_mov_b32 {vr(STAT_G)}, {vr(I_STAT_G)}")
     e.raw(f"v_mov_b32 {vr(STAT_L)}, {vr(I_STAT_L)}")
     e.raw(f"v_mov_b32 {vr(DKV_OFF)}, {vr(I_DKV)}")
@@ -386,7 +395,7 @@ def generate():
     e.raw(f"v_lshlrev_b32 {vr(TMP)}, 4, {vr(TMP)}")
     e.raw(f"v_add_u32 {vr(G16)}, {sr(S_LDS)}, {vr(TMP)}")
     # x[ks] = xbase + (gf16 ^ (ks << 5));  xv[ks] = x[ks] + V tile + wave * 16384
-    e.raw(f"s_lshl_b32 {sr(T_X)}, {sr(S_WAVE)}, 14")
+    e.raw(f"s_lshl_b32 {sr(T_X)}, {sr(S_WAVE)}, {14 if D == 128 else 13}")
     e.raw(f"s_add_u32 {sr(T_X)}, {sr(T_X)}, {VT}")
     for ks in range(KS):
         e.raw(f"v_xor_b32 {vr(TMP)}, {32 * ks}, {vr(I_GF16)}")
@@ -398,7 +407,7 @@ def generate():
         e.raw(f"v_add_u32 {vr(TRLO + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
         e.raw(f"v_xor_b32 {vr(TMP)}, {(64 * db) ^ 32}, {vr(I_LF16)}")
         e.raw(f"v_add_u32 {vr(TRHI + db)}, {vr(I_TRBASE)}, {vr(TMP)}")
-        e.raw(f"v_add_u32 {vr(TRHI + db)}, 2048, {vr(TRHI + db)}")
+        e.raw(f"v_add_u32 {vr(TRHI + db)}, {8 * ROW}, {vr(TRHI + db)}")
     e.comment("---- blocks 0 and 1 requested; accumulators to zero meanwhile")
     for blk in range(2):
         for grp in request_code(blk, blk):
@@ -409,9 +418,9 @@ def generate():
     for i in range(256):
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
     e.comment("statistics of block 0 to LDS stage 0, then block 2 requested (its statistics reuse block 0's registers)")
-    e.raw("s_waitcnt vmcnt(6)")
+    e.raw(f"s_waitcnt vmcnt({NREQ})")
     e.comment("K <- bf16(K * scale * log2(e)): the phase-1 MFMAs then deliver exponents in log2 units")
-    for i in range(0, 64, 4):
+    for i in range(0, 4 * KS * NKB, 4):
         for j in range(4):
             e.raw(f"v_lshlrev_b32 {vr(S0 + 2 * j)}, 16, {vr(i + j)}")
             e.raw(f"v_and_b32 {vr(S0 + 1 + 2 * j)}, 0xffff0000, {vr(i + j)}")
@@ -467,7 +476,7 @@ def generate():
             for db in range(DB):
                 for j in range(4):
                     t = S0 + 4 * (4 * db + j)
-                    e.raw(f"s_waitcnt vmcnt({15 - (4 * db + j)})" if True else "")
+                    e.raw(f"s_waitcnt vmcnt({4 * DB - 1 - (4 * db + j)})")
                     for i in range(4):
                         e.raw(f"v_accvgpr_read_b32 {vr(TMP)}, {ar(accf(db, nb) + 4 * j + i)}")
                         e.raw("s_nop 0")
@@ -487,7 +496,8 @@ def main():
     e = generate()
     clob = [f"v{i}" for i in range(256) if not (IN_V <= i < IN_V + 16)] + [f"a{i}" for i in range(256)]
     clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 94)]
-    write_inc(sys.stdout, "gen_bwd_dkv_asm.py", "ST_DKV_FAST", e, LDS_BYTES, clob)
+    write_inc(sys.stdout, "gen_bwd_dkv_asm.py" + (" 64" if D == 64 else ""), "ST_DKV_FAST" + ("64" if D == 64 else ""), e,
+              LDS_BYTES, clob)
 
 
 if __name__ == "__main__":
