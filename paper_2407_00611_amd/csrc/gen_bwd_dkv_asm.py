@@ -91,7 +91,7 @@ VT = 1024 + 2 * TQ * NS                              # V tile of the workgroup: 
 LDS_BYTES = VT + 256 * ROW
 
 LAT = int(os.environ.get("ST_GEN_DKV_LAT", 3))          # MFMA slots between the issue of an LDS read and its first use
-BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6 if D == 128 else 9))       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
+BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6 if D == 128 else 11))       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
 
 
 

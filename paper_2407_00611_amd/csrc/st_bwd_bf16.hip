@@ -487,12 +487,33 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
         std::swap(a.dv[j], a.dv[j - 1]);
       }
   }
+  hipError_t e = hipSuccess;
   {
-    ProfScope prof(a.dkv_fast ? "bwd_dkv_edge" : "bwd_dkv_bf16", stream);
-    if (a.s.D == 128) hipLaunchKernelGGL(bwd_dkv_bf16_kernel<128>, dim3((unsigned)total_k), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(bwd_dkv_bf16_kernel<64>, dim3((unsigned)total_k), dim3(256), 0, stream, a);
+    // With the fast kernel on, the general one only has the masked and ragged blocks left: chunks whose every
+    // block is the fast kernel's (full tiles, every row sees every key) are left out of its grid, which would
+    // otherwise consist mostly of workgroups that find nothing to do.
+    BwdArgs g = a;
+    if (a.dkv_fast && a.s.Sk % kDkvFastKeys == 0 && a.s.Sq % kDkvFastRows == 0) {
+      g.t.n = 0;
+      for (int c = 0; c < a.t.n; ++c) {
+        const bool all_fast = !a.s.causal || q_pos(a.s, 0) >= a.t.k_offset[c] + a.s.Sk - 1;
+        if (all_fast) continue;
+        g.t.k[g.t.n] = a.t.k[c];
+        g.t.v[g.t.n] = a.t.v[c];
+        g.t.k_offset[g.t.n] = a.t.k_offset[c];
+        g.dk[g.t.n] = a.dk[c];
+        g.dv[g.t.n] = a.dv[c];
+        ++g.t.n;
+      }
+    }
+    if (g.t.n > 0) {
+      ProfScope prof(a.dkv_fast ? "bwd_dkv_edge" : "bwd_dkv_bf16", stream);
+      const unsigned grid = (unsigned)((int64_t)n_kt * a.s.Hkv * a.s.B * g.t.n);
+      if (a.s.D == 128) hipLaunchKernelGGL(bwd_dkv_bf16_kernel<128>, dim3(grid), dim3(256), 0, stream, g);
+      else hipLaunchKernelGGL(bwd_dkv_bf16_kernel<64>, dim3(grid), dim3(256), 0, stream, g);
+      e = hipGetLastError();
+    }
   }
-  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.dkv_fast) {
     e = launch_bwd_dkv_fast(a, stream);
