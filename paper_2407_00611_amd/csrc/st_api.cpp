@@ -423,9 +423,25 @@ st_status st_schedule_report(int32_t P, int32_t C, int64_t B, int64_t N, int64_t
   return ST_OK;
 }
 
+// A fused bf16 forward whose query tiles alone would leave most of the chip idle (fewer than 128 workgroups
+// of 256 queries on 256 compute units) is split over the visited chunks: every query tile gets several
+// workgroups, each with a contiguous share of the chunks and a partial state of its own, and one combine
+// pass folds the states (the chunks of a ring step are independent until the fold, Algorithm 1).
+int fwd_splits(const st_ring_desc* d, int n_visible) {
+  if (d->dtype != ST_BF16 || (d->D != 128 && d->D != 64) || n_visible < 2 || n_visible > st::kMaxTable) return 1;
+  if (d->Sq < st::kQTileFastRows || d->Sk < st::kQTileFastKeys) return 1;
+  const int64_t wgs = (int64_t)d->B * d->Hq * (d->Sq / st::kQTileFastRows);
+  if (wgs >= 128) return 1;
+  int64_t n = 256 / wgs;
+  if (n > n_visible) n = n_visible;
+  if (n > 16) n = 16;
+  return (int)n;
+}
+
 // Workspace layout (each block 256-byte aligned):
 //   forward, stepwise: partial O, partial lse, member O, member lse
-//   forward, fused:    (only when more than one launch is needed) partial O, partial lse
+//   forward, fused:    partial O and partial lse, once (when more than one launch is needed) or once per
+//                      split of an under-filled launch: [O_0, lse_0, O_1, lse_1, ...]
 //   backward:          Delta
 size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t backward) {
   if (d == nullptr) return 0;
@@ -433,7 +449,7 @@ size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t back
   const size_t n_l = align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256);
   if (backward) return n_l;
   if (mode == ST_RING_STEPWISE) return 2 * (n_o + n_l);
-  return n_o + n_l;
+  return (size_t)fwd_splits(d, d->n_chunks) * (n_o + n_l);
 }
 
 st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* order, const int32_t* member_of,
@@ -458,7 +474,14 @@ st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* 
     }
 
   const size_t b_o = align_up((size_t)n_o * sizeof(float), 256), b_l = align_up((size_t)n_l * sizeof(float), 256);
-  const bool need_ws = mode == ST_RING_STEPWISE || n > st::kMaxTable;
+  st::FwdArgs a;
+  memset(&a, 0, sizeof(a));
+  a.s = shape_of(d);
+  a.q = view_of(q);
+  set_table_strides(a.t, d);
+  int splits = mode == ST_RING_FUSED ? fwd_splits(d, n) : 1;
+  if (splits > 1 && !st::fwd_fast_usable(a)) splits = 1;      // only the hand-scheduled kernel pair walks a split table
+  const bool need_ws = mode == ST_RING_STEPWISE || n > st::kMaxTable || splits > 1;
   if (need_ws) {
     if (workspace == nullptr || workspace_bytes < st_ring_workspace_bytes(d, mode, 0)) return fail(ST_ERR_WORKSPACE, "forward workspace needs %zu bytes", st_ring_workspace_bytes(d, mode, 0));
     if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(ST_ERR_ALIGNMENT, "workspace: not 256-byte aligned");
@@ -467,11 +490,31 @@ st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* 
   float* part_o = (float*)ws;
   float* part_l = (float*)(ws + b_o);
 
-  st::FwdArgs a;
-  memset(&a, 0, sizeof(a));
-  a.s = shape_of(d);
-  a.q = view_of(q);
-  set_table_strides(a.t, d);
+  if (mode == ST_RING_FUSED && splits > 1) {
+    a.t.n = n;
+    for (int x = 0; x < n; ++x) {
+      a.t.k[x] = d->k_ptr[vis[x]];
+      a.t.v[x] = d->v_ptr[vis[x]];
+      a.t.k_offset[x] = d->k_offset[vis[x]];
+    }
+    a.o = part_o;
+    a.lse = part_l;
+    a.o_lowp = nullptr;
+    a.n_split = splits;
+    a.split_o = a.split_l = (int64_t)((b_o + b_l) / sizeof(float));
+    ST_HIP(launch_fwd(d->dtype, a, stream), "split forward launch");
+    st::CombineArgs c;
+    memset(&c, 0, sizeof(c));
+    c.n = splits;
+    for (int y = 0; y < splits; ++y) {
+      c.o[y] = part_o + (int64_t)y * a.split_o;
+      c.lse[y] = part_l + (int64_t)y * a.split_l;
+    }
+    c.B = d->B; c.Sq_in = d->Sq; c.Hq = d->Hq; c.D = d->D; c.row0 = 0; c.Sq_out = d->Sq;
+    c.o_out = o_acc; c.lse_out = lse; c.o_lowp = o_lowp;
+    ST_HIP(st::launch_combine(c, d->dtype, stream), "combine launch");
+    return ST_OK;
+  }
 
   if (mode == ST_RING_FUSED) {
     // one launch per kMaxTable visible chunks; further launches go through a partial state + merge

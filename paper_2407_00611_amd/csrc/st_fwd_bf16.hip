@@ -107,11 +107,16 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   auto chunk_t0 = [&](int c) -> int {
     return fast_on ? qtile_fast_tiles(s, fast_row0, a.t.k_offset[c]) : 0;
   };
+  // this workgroup's share of the table and its output state (one share, the whole table, unless the launch is split)
+  int c_lo, c_hi;
+  split_range(a.t.n, a.n_split, blockIdx.y, c_lo, c_hi);
+  float* const out_o = a.o + (int64_t)blockIdx.y * a.split_o;
+  float* const out_lse = a.lse + (int64_t)blockIdx.y * a.split_l;
   bool fast_wrote = false;
   if (fast_on)
-    for (int c = 0; c < a.t.n; ++c) fast_wrote = fast_wrote || chunk_t0(c) > 0;
-  int c_cur = 0, t_cur = 0, n_cur = 0;          // current chunk, tile, tiles in chunk
-  while (c_cur < a.t.n && (n_cur = chunk_tiles(c_cur)) <= (t_cur = chunk_t0(c_cur))) ++c_cur;
+    for (int c = c_lo; c < c_hi; ++c) fast_wrote = fast_wrote || chunk_t0(c) > 0;
+  int c_cur = c_lo, t_cur = 0, n_cur = 0;       // current chunk, tile, tiles in chunk
+  while (c_cur < c_hi && (n_cur = chunk_tiles(c_cur)) <= (t_cur = chunk_t0(c_cur))) ++c_cur;
 
   auto issue_load = [&](int c, int t, int stage) {
     const char* kb = (const char*)a.t.k[c] + ((int64_t)b * a.t.ksb + (int64_t)hk * a.t.ksh) * 2;
@@ -121,17 +126,17 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   };
 
   int buf = 0;
-  if (c_cur < a.t.n) issue_load(c_cur, t_cur, 0);
+  if (c_cur < c_hi) issue_load(c_cur, t_cur, 0);
   __syncthreads();
 
-  while (c_cur < a.t.n) {
+  while (c_cur < c_hi) {
     // next (chunk, tile)
     int c_nxt = c_cur, t_nxt = t_cur + 1, n_nxt = n_cur;
     if (t_nxt >= n_cur) {
       ++c_nxt;
-      while (c_nxt < a.t.n && (n_nxt = chunk_tiles(c_nxt)) <= (t_nxt = chunk_t0(c_nxt))) ++c_nxt;
+      while (c_nxt < c_hi && (n_nxt = chunk_tiles(c_nxt)) <= (t_nxt = chunk_t0(c_nxt))) ++c_nxt;
     }
-    const bool have_next = c_nxt < a.t.n;
+    const bool have_next = c_nxt < c_hi;
     if (have_next) issue_load(c_nxt, t_nxt, buf ^ 1);
 
     // ---- compute on the staged tile
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
       float lse_own = l > 0.f ? m_run[qb] * s.scale + logf(l) : -INFINITY;
       float w_own = inv, w_prev = 0.f;          // weights of this kernel's accumulator and of the stored partial O
       if (fast_wrote) {
-        const float lse_prev = a.lse[srow];
+        const float lse_prev = out_lse[srow];
         const float mx = fmaxf(lse_prev, lse_own);
         if (mx != -INFINITY) {
           const float e_prev = expf(lse_prev - mx), e_own = expf(lse_own - mx);
@@ -274,19 +279,19 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
           o.z = acc_o[db][qb][4 * q4 + 2] * w_own;
           o.w = acc_o[db][qb][4 * q4 + 3] * w_own;
           if (fast_wrote) {
-            const float4 p = *reinterpret_cast<const float4*>(a.o + orow + d);
+            const float4 p = *reinterpret_cast<const float4*>(out_o + orow + d);
             o.x = fmaf(p.x, w_prev, o.x);
             o.y = fmaf(p.y, w_prev, o.y);
             o.z = fmaf(p.z, w_prev, o.z);
             o.w = fmaf(p.w, w_prev, o.w);
           }
-          *reinterpret_cast<float4*>(a.o + orow + d) = o;
+          *reinterpret_cast<float4*>(out_o + orow + d) = o;
           if (a.o_lowp) {
             uint2 w = make_uint2(pack_bf16(o.x, o.y), pack_bf16(o.z, o.w));
             *reinterpret_cast<uint2*>((uint16_t*)a.o_lowp + orow + d) = w;
           }
         }
-      if (g == 0) a.lse[srow] = lse_own;
+      if (g == 0) out_lse[srow] = lse_own;
     }
   }
 }
@@ -718,7 +723,7 @@ hipError_t launch_fwd_bf16(const FwdArgs& a_in, hipStream_t stream) {
     const char* e = getenv("ST_FWD_FAST");
     return e ? atoi(e) : 1;
   }();
-  if (fast_env && fwd_fast_usable(a_in)) {
+  if ((fast_env || a_in.n_split > 1) && fwd_fast_usable(a_in)) {
     // fully visible full tiles by the hand-scheduled kernel, then everything else (merged into its result)
     FwdArgs a = a_in;
     a.fwd_fast = 1;
@@ -728,10 +733,12 @@ hipError_t launch_fwd_bf16(const FwdArgs& a_in, hipStream_t stream) {
     const int n_qt = (a.s.Sq + 127) / 128;
     const int64_t total = (int64_t)n_qt * a.s.Hq * a.s.B;
     if (total > 0x7fffffff) return hipErrorInvalidValue;
-    if (a.s.D == 128) hipLaunchKernelGGL((fwd_bf16_kernel<128, 32>), dim3((unsigned)total), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL((fwd_bf16_kernel<64, 32>), dim3((unsigned)total), dim3(256), 0, stream, a);
+    const dim3 grid((unsigned)total, (unsigned)(a.n_split > 1 ? a.n_split : 1));
+    if (a.s.D == 128) hipLaunchKernelGGL((fwd_bf16_kernel<128, 32>), grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL((fwd_bf16_kernel<64, 32>), grid, dim3(256), 0, stream, a);
     return hipGetLastError();
   }
+  if (a_in.n_split > 1) return hipErrorInvalidValue;   // only the fast / edge pair walks a split table
   const FwdArgs& a = a_in;
   // head size 64: the two-wavefronts-per-SIMD kernel is the faster one (21.0 against 28.3 ms on the 24-head,
   // 16384 x 131072 full-mask share); head size 128 without the fast path: the pipelined kernel

@@ -58,7 +58,19 @@ struct FwdArgs {
   float* lse;      // fp32 [B,Hq,Sq]
   void* o_lowp;    // nullable, [B,Sq,Hq,D] in the storage dtype
   int32_t fwd_fast;  // 1: the fast forward kernel ran first and owns the tiles qtile_fast_tiles describes
+  // Under-filled launches: n_split > 1 gives every query tile n_split workgroups (blockIdx.y), each walking a
+  // contiguous share of the table and writing its own partial state at o + y * split_o, lse + y * split_l
+  // (floats); the states are combined afterwards.  0 or 1: one workgroup walks the whole table.
+  int32_t n_split;
+  int64_t split_o, split_l;
 };
+
+// table entries [lo, hi) of split y
+__host__ __device__ inline void split_range(int n, int n_split, int y, int& lo, int& hi) {
+  if (n_split <= 1) { lo = 0; hi = n; return; }
+  lo = (int)((int64_t)n * y / n_split);
+  hi = (int)((int64_t)n * (y + 1) / n_split);
+}
 
 struct BwdArgs {
   Shape s;
