@@ -151,8 +151,9 @@ st_status st_attn_delta(const st_block_desc* desc, const st_tensor* d_o, const s
  *   dQ += scale dS k,  dK += scale dS^T q   (dK, dV summed over the query heads of a KV group).
  *   dq_acc fp32 [B,Sq,Hq,D]   ACCUMULATED (+=): the circulating query gradient
  *   dk_acc, dv_acc fp32 [B,Sk,Hkv,D] ACCUMULATED (+=): stay with the chunk
- * The caller zeroes the accumulators once.  dq_acc is updated with floating-point atomics
- * in the bf16 path, so its low-order bits may differ from run to run. */
+ * The caller zeroes the accumulators once.  Every accumulator element is owned by one workgroup per
+ * launch (read, add, write; no atomics), so results are bit-reproducible; calls that add into the same
+ * accumulator must be ordered on one stream. */
 st_status st_attn_block_bwd(const st_block_desc* desc, const st_tensor* q, const st_tensor* k,
                             const st_tensor* v, const st_tensor* d_o, const float* lse_final,
                             const float* delta, float* dq_acc, float* dk_acc, float* dv_acc,
