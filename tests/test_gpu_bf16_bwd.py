@@ -134,6 +134,9 @@ BHSD_CASES = [
     si.Workload("fast_bhsd_64chunks", 97, "bf16", 2, 4, 2, 128, 288, 64, 64, 64 * 64 - 288, True, True),
     # 320-key chunks: the dK/dV loop as well (one full 256-key tile per chunk)
     si.Workload("fast_bhsd_dkv", 98, "bf16", 2, 4, 2, 128, 288, 320, 3, 3 * 320 - 288, True, True),
+    # the same at head size 64
+    si.Workload("fast64_bhsd_64chunks", 97, "bf16", 2, 4, 2, 64, 288, 64, 64, 64 * 64 - 288, True, True),
+    si.Workload("fast64_bhsd_dkv", 98, "bf16", 2, 4, 2, 64, 288, 320, 3, 3 * 320 - 288, True, True),
 ]
 
 
