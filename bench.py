@@ -307,10 +307,11 @@ def cpu_baseline(w, inp, met=None) -> dict:
     import synth_inputs as si
     from oracle import attention as oa
 
-    rows_per_head = 128 if w.Sq >= 128 else w.Sq
     G = w.Hq // w.Hkv
     heads = list(range(min(G, w.Hq)))                      # the query heads of KV head 0
     met = list(range(w.n_chunks)) if met is None else list(met)
+    # about 1e9 (query, key) pairs: some 10 - 15 s of fp64 numpy on the machine's host cores
+    rows_per_head = int(max(1, min(w.Sq, 1.1e9 // (len(heads) * w.Sk * len(met)))))
     k_pos = [np.arange(w.Sk, dtype=np.int64) + w.k_offset(j) for j in met]
 
     def kv_head0(bits_list, f32_list):
