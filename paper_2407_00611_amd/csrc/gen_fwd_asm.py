@@ -80,6 +80,9 @@ BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 7 if D == 128 else 13))
 BRANCH_SLOT = 2 * DB + 1                             # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
 
 
+STUBS = []                                           # (call label, return label, P buffer) of every reference test
+
+
 class Pipe:
     def __init__(self, e):
         self.e = e
@@ -240,12 +243,13 @@ def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, pr
                 mi[0] += 1
                 units += 1
             if k == BRANCH_SLOT:
-                l_cont = e.label("cont")
+                # the common path falls through; the call sits out of line behind the loop (a taken branch costs a refetch)
+                l_call, l_back = e.label("call"), e.label("back")
                 e.raw(f"v_cmp_gt_f32 vcc, {vr(DMAX)}, {vr(GAPR)}")
                 e.raw("s_cmp_lg_u64 vcc, 0")
-                e.raw(f"s_cbranch_scc0 {l_cont}")
-                e.raw(f"s_swappc_b64 {sr(T_RET, 2)}, {sr(T_RARE + 2 * par, 2)}")
-                e.raw(l_cont + ":")
+                e.raw(f"s_cbranch_scc1 {l_call}")
+                e.raw(l_back + ":")
+                STUBS.append((l_call, l_back, par))
             while k > BRANCH_SLOT and vi[0] < len(valu_e) and units + valu_e[vi[0]][2] <= BUDGET:
                 e.valu(valu_e[vi[0]][0], valu_e[vi[0]][1])
                 units += valu_e[vi[0]][2]
@@ -473,6 +477,10 @@ def generate():
         e.raw("s_nop 7")                 # the exponentials above were not hidden under a second MFMA group
         gen_iter(p, (u, 1), None, None, 1, sq + 1, do_a=False, do_valu=False, prefetch=False)
         e.raw(f"s_branch {l_done}")
+    for l_call, l_back, par in STUBS:
+        e.raw(l_call + ":")
+        e.raw(f"s_swappc_b64 {sr(T_RET, 2)}, {sr(T_RARE + 2 * par, 2)}")
+        e.raw(f"s_branch {l_back}")
     for b in range(2):
         e.raw(l_rare[b] + ":")
         gen_rescale_routine(e, b)
