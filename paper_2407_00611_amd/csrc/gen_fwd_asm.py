@@ -80,6 +80,7 @@ BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 7 if D == 128 else 13))
 BRANCH_SLOT = 2 * DB + 1                             # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
 
 
+NEXT_STUBS = []                                      # (label, return label) of every switch to the next chunk
 STUBS = []                                           # (call label, return label, P buffer) of every reference test
 
 
@@ -181,7 +182,7 @@ def valu_exp(sbuf, pbuf):
     return out
 
 
-def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, prefetch=True):
+def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, prefetch=True, side=None):
     """Block i = cur, i+1 = nxt (its V^T is prefetched at the tail), i+2 = nxt2 (its K feeds group A).
     par = i % 2: P(i) sits in P buffer par, S(i+1) in score buffer 1 - par, S(i+2) goes to score buffer par."""
     e = p.e
@@ -236,6 +237,10 @@ def gen_iter(p, cur, nxt, nxt2, par, seq, do_a=True, do_valu=True, head=None, pr
             n0 = len(e.ds)
             fn()
             units += len(e.ds) - n0
+        if side and k in side:                           # tile request / stream bookkeeping spread under the MFMAs
+            for ln in side[k]:
+                e.raw(ln)
+            units += 2
         if do_valu:
             # S(i+1) was written by the last group of the block before: first reader three MFMA issues later
             while 3 <= k <= BRANCH_SLOT and mi[0] < len(valu_m) and (units < BUDGET or k == BRANCH_SLOT):
@@ -310,30 +315,43 @@ def gen_rescale_routine(e, pbuf):
     e.raw(f"s_setpc_b64 {sr(T_RET, 2)}")
 
 
-def gen_dma(e, stage):
+def dma_groups(stage):
+    """The direct-to-LDS loads of one K / V tile into LDS stage `stage`: one [M0 setup, gap, load] group per load."""
+    g = []
     for j in range(NDMA):
-        e.raw(f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}")
-        e.raw("s_nop 0")
-        e.raw(f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}")
-        e.raw(f"s_add_u32 m0, {sr(T_M0)}, {VT(stage) + 4096 * j}")
-        e.raw("s_nop 0")
-        e.raw(f"global_load_lds_dwordx4 {vr(VOFF + j)}, {sr(D_VPTR, 2)}")
+        g.append([f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}", "s_nop 0",
+                  f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}"])
+        g.append([f"s_add_u32 m0, {sr(T_M0)}, {VT(stage) + 4096 * j}", "s_nop 0",
+                  f"global_load_lds_dwordx4 {vr(VOFF + j)}, {sr(D_VPTR, 2)}"])
+    return g
+
+
+def advance_lines(e):
+    """Move the K / V stream to the next tile of the walk (it stays on the last tile once all S_NT tiles have been
+    requested).  The common path falls through; the switch to the next chunk of the table sits out of line."""
     l_skip, l_next = e.label("skip"), e.label("nextchunk")
-    e.raw(f"s_add_u32 {sr(T_X)}, {sr(D_IDX)}, 1")
-    e.raw(f"s_cmp_ge_u32 {sr(T_X)}, {sr(S_NT)}")
-    e.raw(f"s_cbranch_scc1 {l_skip}")
-    e.raw(f"s_mov_b32 {sr(D_IDX)}, {sr(T_X)}")
-    e.raw(f"s_sub_u32 {sr(D_LEFT)}, {sr(D_LEFT)}, 1")
-    e.raw(f"s_cmp_eq_u32 {sr(D_LEFT)}, 0")
-    e.raw(f"s_cbranch_scc1 {l_next}")
-    e.raw(f"s_add_u32 {sr(D_KPTR)}, {sr(D_KPTR)}, {sr(S_KTILE)}")
-    e.raw(f"s_addc_u32 {sr(D_KPTR + 1)}, {sr(D_KPTR + 1)}, 0")
-    e.raw(f"s_add_u32 {sr(D_VPTR)}, {sr(D_VPTR)}, {sr(S_VTILE)}")
-    e.raw(f"s_addc_u32 {sr(D_VPTR + 1)}, {sr(D_VPTR + 1)}, 0")
-    e.raw(f"s_branch {l_skip}")
-    e.raw(l_next + ":")
-    gen_table_entry(e)
-    e.raw(l_skip + ":")
+    NEXT_STUBS.append((l_next, l_skip))
+    return [f"s_add_u32 {sr(T_X)}, {sr(D_IDX)}, 1",
+            f"s_cmp_ge_u32 {sr(T_X)}, {sr(S_NT)}",
+            f"s_cbranch_scc1 {l_skip}",
+            f"s_mov_b32 {sr(D_IDX)}, {sr(T_X)}",
+            f"s_sub_u32 {sr(D_LEFT)}, {sr(D_LEFT)}, 1",
+            f"s_cmp_eq_u32 {sr(D_LEFT)}, 0",
+            f"s_cbranch_scc1 {l_next}",
+            f"s_add_u32 {sr(D_KPTR)}, {sr(D_KPTR)}, {sr(S_KTILE)}",
+            f"s_addc_u32 {sr(D_KPTR + 1)}, {sr(D_KPTR + 1)}, 0",
+            f"s_add_u32 {sr(D_VPTR)}, {sr(D_VPTR)}, {sr(S_VTILE)}",
+            f"s_addc_u32 {sr(D_VPTR + 1)}, {sr(D_VPTR + 1)}, 0",
+            l_skip + ":"]
+
+
+def gen_dma(e, stage):
+    """Request a tile and advance the stream, in one piece (prologue)."""
+    for grp in dma_groups(stage):
+        for ln in grp:
+            e.raw(ln)
+    for ln in advance_lines(e):
+        e.raw(ln)
 
 
 def gen_table_entry(e):
@@ -458,11 +476,12 @@ def generate():
         drains.append((l_drain, u, p.snapshot(), seq))
 
         def head(u=u):
-            # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: request tile T + 3
+            # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: tile T + 3 may be requested
             e.raw(f"s_waitcnt vmcnt({2 * NDMA})")
             e.raw("s_barrier")
-            gen_dma(e, (u + 3) % NS)
-        leftover += gen_iter(p, (u, 0), (u, 1), (un, 0), 0, seq, head=head)
+        side = {k: grp for k, grp in enumerate(dma_groups((u + 3) % NS))}
+        side[2 * NDMA] = advance_lines(e)
+        leftover += gen_iter(p, (u, 0), (u, 1), (un, 0), 0, seq, head=head, side=side)
         seq += 1
         leftover += gen_iter(p, (u, 1), (un, 0), (un, 1), 1, seq)
         seq += 1
@@ -477,6 +496,10 @@ def generate():
         e.raw("s_nop 7")                 # the exponentials above were not hidden under a second MFMA group
         gen_iter(p, (u, 1), None, None, 1, sq + 1, do_a=False, do_valu=False, prefetch=False)
         e.raw(f"s_branch {l_done}")
+    for l_next, l_skip in NEXT_STUBS:
+        e.raw(l_next + ":")
+        gen_table_entry(e)
+        e.raw(f"s_branch {l_skip}")
     for l_call, l_back, par in STUBS:
         e.raw(l_call + ":")
         e.raw(f"s_swappc_b64 {sr(T_RET, 2)}, {sr(T_RARE + 2 * par, 2)}")
