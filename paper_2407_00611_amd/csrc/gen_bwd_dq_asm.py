@@ -126,7 +126,7 @@ def read_kt(p, stage, kb, m, db, seq):
     p.e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(hi + db)} offset:{off}", tag)
 
 
-def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, prefetched=True):
+def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, prefetched=True, side=None):
     """cur / nxt / nxt2 = (stage, kb) of blocks i, i+1, i+2 (nxt2 only for the prefetch at the tail).
     pbuf = score buffer that holds P(i); S(i+1) goes to the other one.  `head` is emitted in front of the
     first MFMA (barrier and DMA of a new tile).  seq numbers the block for fragment tags: tags of block
@@ -230,6 +230,10 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
             n0 = len(e.ds)
             fn()
             units += len(e.ds) - n0
+        if side and k in side:                           # tile request / stream bookkeeping spread under the MFMAs
+            for ln in side[k]:
+                e.raw(ln)
+            units += 2
         while vi[0] < len(valu) and valu[vi[0]][0] <= k and units + valu[vi[0]][3] <= BUDGET:
             units += emit_valu(valu[vi[0]])
             vi[0] += 1
@@ -240,31 +244,46 @@ def gen_block(p, cur, nxt, nxt2, pbuf, seq, do_b=True, do_ac=True, head=None, pr
     assert vi[0] == len(valu), f"VALU work left over: {len(valu) - vi[0]}"
 
 
-def gen_dma(e, stage):
+NEXT_STUBS = []                                      # (label, return label) of every switch to the next chunk
+
+
+def dma_groups(stage):
+    """The direct-to-LDS loads of one K / V tile into LDS stage `stage`: one [M0 setup, gap, load] group per load."""
+    g = []
     for j in range(NDMA):
-        e.raw(f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}")
-        e.raw("s_nop 0")
-        e.raw(f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}")
-        e.raw(f"s_add_u32 m0, {sr(T_M0)}, {VT(stage) + 4096 * j}")
-        e.raw("s_nop 0")
-        e.raw(f"global_load_lds_dwordx4 {vr(VOFF + j)}, {sr(D_VPTR, 2)}")
-    # next tile of the walk; stays on the last tile once all S_NT tiles have been requested
+        g.append([f"s_add_u32 m0, {sr(T_M0)}, {KT(stage) + 4096 * j}", "s_nop 0",
+                  f"global_load_lds_dwordx4 {vr(KOFF + j)}, {sr(D_KPTR, 2)}"])
+        g.append([f"s_add_u32 m0, {sr(T_M0)}, {VT(stage) + 4096 * j}", "s_nop 0",
+                  f"global_load_lds_dwordx4 {vr(VOFF + j)}, {sr(D_VPTR, 2)}"])
+    return g
+
+
+def advance_lines(e):
+    """Move the K / V stream to the next tile of the walk (it stays on the last tile once all S_NT tiles have been
+    requested).  The common path falls through; the switch to the next chunk of the table sits out of line."""
     l_skip, l_next = e.label("skip"), e.label("nextchunk")
-    e.raw(f"s_add_u32 {sr(T_X)}, {sr(D_IDX)}, 1")
-    e.raw(f"s_cmp_ge_u32 {sr(T_X)}, {sr(S_NT)}")
-    e.raw(f"s_cbranch_scc1 {l_skip}")
-    e.raw(f"s_mov_b32 {sr(D_IDX)}, {sr(T_X)}")
-    e.raw(f"s_sub_u32 {sr(D_LEFT)}, {sr(D_LEFT)}, 1")
-    e.raw(f"s_cmp_eq_u32 {sr(D_LEFT)}, 0")
-    e.raw(f"s_cbranch_scc1 {l_next}")
-    e.raw(f"s_add_u32 {sr(D_KPTR)}, {sr(D_KPTR)}, {sr(S_KTILE)}")
-    e.raw(f"s_addc_u32 {sr(D_KPTR + 1)}, {sr(D_KPTR + 1)}, 0")
-    e.raw(f"s_add_u32 {sr(D_VPTR)}, {sr(D_VPTR)}, {sr(S_VTILE)}")
-    e.raw(f"s_addc_u32 {sr(D_VPTR + 1)}, {sr(D_VPTR + 1)}, 0")
-    e.raw(f"s_branch {l_skip}")
-    e.raw(l_next + ":")
-    gen_table_entry(e)
-    e.raw(l_skip + ":")
+    NEXT_STUBS.append((l_next, l_skip))
+    return [f"s_add_u32 {sr(T_X)}, {sr(D_IDX)}, 1",
+            f"s_cmp_ge_u32 {sr(T_X)}, {sr(S_NT)}",
+            f"s_cbranch_scc1 {l_skip}",
+            f"s_mov_b32 {sr(D_IDX)}, {sr(T_X)}",
+            f"s_sub_u32 {sr(D_LEFT)}, {sr(D_LEFT)}, 1",
+            f"s_cmp_eq_u32 {sr(D_LEFT)}, 0",
+            f"s_cbranch_scc1 {l_next}",
+            f"s_add_u32 {sr(D_KPTR)}, {sr(D_KPTR)}, {sr(S_KTILE)}",
+            f"s_addc_u32 {sr(D_KPTR + 1)}, {sr(D_KPTR + 1)}, 0",
+            f"s_add_u32 {sr(D_VPTR)}, {sr(D_VPTR)}, {sr(S_VTILE)}",
+            f"s_addc_u32 {sr(D_VPTR + 1)}, {sr(D_VPTR + 1)}, 0",
+            l_skip + ":"]
+
+
+def gen_dma(e, stage):
+    """Request a tile and advance the stream, in one piece (prologue)."""
+    for grp in dma_groups(stage):
+        for ln in grp:
+            e.raw(ln)
+    for ln in advance_lines(e):
+        e.raw(ln)
 
 
 def gen_table_entry(e):
@@ -355,12 +374,13 @@ def generate():
         un = (u + 1) % NS
 
         def head(u=u):
-            # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: request tile T + 3
+            # tile T + 1 has landed everywhere and nobody reads tile T - 1 any more: tile T + 3 may be requested
             e.raw(f"s_waitcnt vmcnt({2 * NDMA})")
             e.raw("s_barrier")
-            gen_dma(e, (u + 3) % NS)
+        side = {k: grp for k, grp in enumerate(dma_groups((u + 3) % NS))}
+        side[2 * NDMA] = advance_lines(e)
         # the head sits between the tail prefetch of the block before and this block's first MFMA
-        gen_block(p, (u, 0), (u, 1), (un, 0), 0, seq, head=head)
+        gen_block(p, (u, 0), (u, 1), (un, 0), 0, seq, head=head, side=side)
         seq += 1
         l_drain = e.label("drain")
         e.raw(f"s_cmp_eq_u32 {sr(T_REM)}, 1")
@@ -380,6 +400,10 @@ def generate():
         e.raw("s_nop 7")
         gen_block(p, (u, 1), None, None, 1, sq, do_ac=False)
         e.raw(f"s_branch {l_done}")
+    for l_next, l_skip in NEXT_STUBS:
+        e.raw(l_next + ":")
+        gen_table_entry(e)
+        e.raw(f"s_branch {l_skip}")
     e.raw(l_done + ":")
     e.raw("s_waitcnt vmcnt(0) lgkmcnt(0)")
     e.comment("---- epilogue: dq_acc += scale * dQ; lane = query row, 4 consecutive d per 16-byte access")
