@@ -68,7 +68,7 @@ TBL = 2 * TILE * NS                                     # 64 entries x 32 bytes:
 LDS_BYTES = TBL + 2048
 
 LAT = int(os.environ.get("ST_GEN_DQ_LAT", 3))
-BUDGET = int(os.environ.get("ST_GEN_DQ_BUDGET", 6 if D == 128 else 7))
+BUDGET = int(os.environ.get("ST_GEN_DQ_BUDGET", 5 if D == 128 else 7))
 
 
 class Pipe:

@@ -76,7 +76,7 @@ TBL = 2 * TILE * NS
 LDS_BYTES = TBL + 2048
 
 LAT = int(os.environ.get("ST_GEN_FWD_LAT", 3))
-BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 7 if D == 128 else 13))
+BUDGET = int(os.environ.get("ST_GEN_FWD_BUDGET", 6 if D == 128 else 13))
 BRANCH_SLOT = 2 * DB + 1                             # the reference test sits behind this MFMA slot (m = 1, db = 0 issued)
 
 
