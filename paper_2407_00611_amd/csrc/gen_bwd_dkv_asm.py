@@ -169,7 +169,7 @@ def plan_reads(e, pool, u, seq):
     """LDS reads of the block on stage u, by the MFMA slot behind which they are issued; negative slots are
     issued by the block before (slot + 64) or by the prologue."""
     qt, dot_, stats = QT(u), DOT(u), STATS + 256 * u
-    reads = {k: [] for k in range(-LAT, NSLOT)}
+    reads = {k: [] for k in range(-EARLY, NSLOT)}
 
     def plan(first_use, fn):
         reads[first_use - LAT].append(fn)
@@ -187,17 +187,22 @@ def plan_reads(e, pool, u, seq):
             e.ds_read(f"ds_read_b64_tr_b16 {vr(r + 2, 2)}, {vr(TRHI + db)} offset:{tile_imm + 16 * ROW * m}", tag)
         return f
 
-    def rd_stat(tag, base_reg, imm):
+    def rd_stat(tag, base_reg, imm, js):
         def f():
-            for j in range(4):
+            for j in js:
                 e.ds_read(f"ds_read_b128 {vr(base_reg + 4 * j, 4)}, {vr(G16)} offset:{imm + 32 * j}", f"{tag}{j}")
         return f
 
     for ks in range(KS):
         plan(2 * ks, rd_nat(f"{seq}q{ks}", qt, ks, X, NKB))
         if ks == 0:
-            plan(0, rd_stat(f"{seq}nl", NL, stats))
-            plan(1, rd_stat(f"{seq}nd", ND, stats + 128))
+            # the statistics were published before the barrier of the block before: read them early, two reads per
+            # slot, instead of in one burst in front of the block (nl is free from slot 2 on, nd shares its registers
+            # with the packed P, last read in phase 3)
+            reads[-EARLY].append(rd_stat(f"{seq}nl", NL, stats, (0, 1)))
+            reads[-EARLY + 1].append(rd_stat(f"{seq}nl", NL, stats, (2, 3)))
+            reads[-EARLY + 4].append(rd_stat(f"{seq}nd", ND, stats + 128, (0, 1)))
+            reads[-EARLY + 5].append(rd_stat(f"{seq}nd", ND, stats + 128, (2, 3)))
     for ks in range(KS):
         base = P2 + 2 * ks
         plan(base, rd_nat(f"{seq}do{ks}", dot_, ks, X, NKB))
@@ -211,6 +216,8 @@ def plan_reads(e, pool, u, seq):
     return reads
 
 
+EARLY = 12                # the next block's statistics are read from this many slots before the end of a block on
+assert NSLOT - EARLY > P3 - 1 and NSLOT - EARLY + 4 >= P4, "statistics reads: behind the barrier, nd behind phase 3"
 SYNC_SLOT = P3 - 1        # the barrier sits behind this MFMA slot (end of phase 2)
 PUBLISH_SLOT = P3 - 6     # wait for the next block's loads and write its statistics behind this slot
 
@@ -440,9 +447,10 @@ def generate():
 
     plans = [plan_reads(e, pool, u, u) for u in range(NS)] + [None]
     # what block 0 of every pass through the loop expects to be in flight: its first reads
-    for k in range(-LAT, 0):
+    for k in range(-EARLY, 0):
         for fn in plans[0][k]:
             fn()
+    e.need("0nd3")              # as at the end of a pass through the loop: the early statistics reads have completed
     l_loop, l_done = e.label("loop"), e.label("done")
     e.raw(l_loop + ":")
     entry = list(e.ds)
