@@ -87,8 +87,6 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
   }
   const int wg_last_row = min(qt * kQ_BM + kQ_BM, s.Sq) - 1;
   const int wave_first_row = q_row0;
-  const int wave_last_row = min(q_row0 + kQ_WQ, s.Sq) - 1;
-  const bool wave_live = wave_last_row >= wave_first_row;
 
   f32x16 acc[DB][QB];
 #pragma unroll

@@ -76,8 +76,6 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   // rows of this workgroup / wavefront that exist
   const int wg_last_row = min(qt * kBM + kBM, s.Sq) - 1;
   const int wave_first_row = q_row0;
-  const int wave_last_row = min(q_row0 + kWQ, s.Sq) - 1;   // < wave_first_row if the wavefront has no rows
-  const bool wave_live = wave_last_row >= wave_first_row;
 
   f32x16 acc_o[DB][QB];
 #pragma unroll
@@ -314,7 +312,7 @@ struct TileCursor {
 
 template <int D>
 __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
-  constexpr int kWQ = 64, kBM = 256, QB = 2, KB = 2, KS = D / 16, DB = D / 32, NS = 4;
+  constexpr int kWQ = 64, kBM = 256, QB = 2, KS = D / 16, DB = D / 32, NS = 4;
   constexpr int kTile = kBN * D * 2, kStage = 2 * kTile;
   constexpr int kDmaPerTile = 2 * DmaPlan<D, kBN>::PER_WAVE;   // K + V instructions per wavefront
   __shared__ __attribute__((aligned(1024))) char smem_raw[NS * kStage];

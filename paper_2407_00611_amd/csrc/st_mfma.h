@@ -178,10 +178,15 @@ __device__ __forceinline__ void stage_dma(const char* base, int64_t row_stride_e
 // The same staging with the DMA written as inline asm: the compiler then does not track it, so it
 // places no vmcnt wait in front of later LDS reads and several tiles can be in flight; the caller
 // waits explicitly (wait_vmcnt<N>: at most N of this wavefront's loads still outstanding).
+// (m0 is a reserved register: naming it as a clobber draws a warning, but the surrounding code is compiled C++
+// that may use m0 itself, so the statement says what it overwrites)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16_asm(const char* src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :: "s"(lds_addr), "v"(src) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
