@@ -449,7 +449,9 @@ size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t back
   const size_t n_l = align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256);
   if (backward) return n_l;
   if (mode == ST_RING_STEPWISE) return 2 * (n_o + n_l);
-  return (size_t)fwd_splits(d, d->n_chunks) * (n_o + n_l);
+  // the split grows with the number of visited chunks up to one launch's table, and any subset may be visited
+  const int n_most = d->n_chunks < st::kMaxTable ? d->n_chunks : st::kMaxTable;
+  return (size_t)fwd_splits(d, n_most) * (n_o + n_l);
 }
 
 st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* order, const int32_t* member_of,

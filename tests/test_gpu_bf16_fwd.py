@@ -123,3 +123,44 @@ def test_empty_and_future_chunks():
     assert not o.any() and torch.isneginf(l).all()
     o, l, ol = st.st_ring_fwd(q, ks, vs, 0, [1000], True, w.scale, [0])            # whole share invisible
     assert not o.any() and torch.isneginf(l).all() and not ol.any()
+
+
+MANY = [
+    # name, D, Sq, Sk, chunks, visited (None: all)
+    ("three_launches_d128", 128, 300, 64, 150, None),
+    ("subset_of_many_d128", 128, 300, 64, 150, 50),
+    ("most_chunks_d64", 64, 70, 16, 256, None),
+]
+
+
+@pytest.mark.parametrize("case", MANY, ids=[c[0] for c in MANY])
+def test_many_chunks_forward_and_backward(case):
+    """More chunks than one launch's table holds (64), up to the most a call accepts (256), and a visited subset
+    of a long table: the fused driver walks them in several launches, or splits one under-filled launch."""
+    name, D, Sq, Sk, n, visited = case
+    w = si.Workload(name, 85, "bf16", 1, 2, 1, D, Sq, Sk, n, n * Sk - Sq - 40, True, True)
+    inp = si.make_inputs(w, threads=8)
+    q, ks, vs, d_o = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(n)]
+    order = list(range(n - 1, -1, -1)) if visited is None else list(range(n - 1, -1, -3))[:visited]
+    sub = sorted(order)
+    o_ref, lse_ref = oa.attention_forward(inp.q, [inp.k[j] for j in sub], [inp.v[j] for j in sub], q_pos,
+                                          [k_pos[j] for j in sub], True, w.scale)
+    dq_ref, dk_ref, dv_ref = oa.attention_backward(inp.q, [inp.k[j] for j in sub], [inp.v[j] for j in sub], inp.d_o, q_pos,
+                                                   [k_pos[j] for j in sub], True, w.scale)
+    o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, True, w.scale, order, None, st.ST_RING_FUSED)
+    dq = torch.zeros_like(o)
+    dk = [torch.zeros(k.shape, device="cuda") for k in ks]
+    dv = [torch.zeros(k.shape, device="cuda") for k in ks]
+    st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, True, w.scale, order, dq, dk, dv, st.ST_RING_FUSED)
+    torch.cuda.synchronize()
+    assert_close(host(o), o_ref, "bf16", "o")
+    assert_close(host(lse), lse_ref, "bf16", "lse", lse=True)
+    assert torch.equal(o_low, o.to(torch.bfloat16))
+    assert_close(host(dq), dq_ref, "bf16", "dq")
+    for x, j in enumerate(sub):
+        assert_close(host(dk[j]), dk_ref[x], "bf16", f"dk {j}")
+        assert_close(host(dv[j]), dv_ref[x], "bf16", f"dv {j}")
+    for j in set(range(n)) - set(sub):
+        assert float(dk[j].abs().max()) == 0.0 and float(dv[j].abs().max()) == 0.0
