@@ -116,3 +116,21 @@ def test_validation_fails_before_any_launch():
 def test_empty_problems_are_ok_without_a_gpu():
     assert _call_fwd(_desc(Sq=0), q=0, o=0, lse=0) == 0
     assert _call_fwd(_desc(B=0), q=0, k=0, v=0, o=0, lse=0) == 0
+
+
+def test_forward_workspace_covers_every_visited_subset():
+    """An under-filled fused forward is split over the visited chunks; the workspace the library asks for must be
+    enough for any subset of the table the caller may then visit (host logic only: no launch)."""
+    import torch
+
+    def need(n_chunks, Sq=300, Hq=2, D=128, Sk=64):
+        q = torch.zeros((1, Sq, Hq, D), dtype=torch.bfloat16)
+        ks = [torch.zeros((1, Sk, 1, D), dtype=torch.bfloat16) for _ in range(n_chunks)]
+        return st.st_ring_workspace_bytes(q, ks, ks, 0, [Sk * j for j in range(n_chunks)], True, 0.1, st.ST_RING_FUSED, False)
+
+    one = need(1)
+    assert one > 0 and need(2) == 2 * one                    # two chunks: two partial states
+    sizes = [need(n) for n in (1, 2, 5, 16, 50, 64)]
+    assert sizes == sorted(sizes)                             # grows with the table ...
+    assert need(150) == need(64) == need(256)                 # ... up to one launch's table, and stays there
+    assert need(64, Sq=4096, Hq=32) == need(1, Sq=4096, Hq=32)  # enough query tiles to fill the chip: never split
