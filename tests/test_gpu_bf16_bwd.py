@@ -177,3 +177,35 @@ def test_fast_kernels_strided_layout(w):
     for j in range(w.n_chunks):
         assert_close(host(a[3][j]), dk_r[j], "bf16", f"dk[{j}]")
         assert_close(host(a[4][j]), dv_r[j], "bf16", f"dv[{j}]")
+
+
+def test_degenerate_shapes():
+    """Nothing to do is legal everywhere: no query rows, batch 0, an empty visit list, zero elements to cast."""
+    dev = "cuda"
+    for B, Sq in ((1, 0), (0, 64)):
+        q = torch.zeros((B, Sq, 2, 128), dtype=torch.bfloat16, device=dev)
+        k = torch.zeros((B, 64, 1, 128), dtype=torch.bfloat16, device=dev)
+        o, lse = st.st_attn_block_fwd(q, k, k, 0, 0, True, 0.1)
+        assert o.shape == (B, Sq, 2, 128) and lse.shape == (B, 2, Sq)
+        o, lse, low = st.st_ring_fwd(q, [k], [k], 0, [0], True, 0.1, [0])
+        delta = st.st_attn_delta(q, o)
+        dq = torch.zeros_like(o)
+        dk, dv = torch.zeros(k.shape, device=dev), torch.zeros(k.shape, device=dev)
+        st.st_attn_block_bwd(q, k, k, q, lse, delta, 0, 0, True, 0.1, dq, dk, dv)
+        st.st_ring_bwd(q, [k], [k], q, low, lse, 0, [0], True, 0.1, [0], dq, [dk], [dv])
+        st.st_attn_merge(o, lse, torch.zeros_like(o), torch.zeros_like(lse))
+        oc, lc = st.st_attn_combine([o, o.clone()], [lse, lse.clone()])
+        assert oc.shape == o.shape and lc.shape == lse.shape
+        assert st.st_cast_from_f32(o, st.ST_BF16).shape == o.shape
+        torch.cuda.synchronize()
+        assert not dk.any() and not dv.any()
+    # an empty visit list: the state is the empty state, the gradients stay as they were
+    q = torch.randn((1, 40, 2, 128), device=dev).to(torch.bfloat16)
+    k = torch.randn((1, 64, 1, 128), device=dev).to(torch.bfloat16)
+    o, lse, low = st.st_ring_fwd(q, [k], [k], 0, [0], False, 0.1, [])
+    dq = torch.ones((1, 40, 2, 128), device=dev)
+    dk, dv = torch.ones(k.shape, device=dev), torch.ones(k.shape, device=dev)
+    st.st_ring_bwd(q, [k], [k], q, low, lse, 0, [0], False, 0.1, [], dq, [dk], [dv])
+    torch.cuda.synchronize()
+    assert not o.any() and torch.isneginf(lse).all() and not low.any()
+    assert bool((dq == 1).all()) and bool((dk == 1).all()) and bool((dv == 1).all())
