@@ -38,7 +38,7 @@ TILE = 64 * ROW                                      # one 64-key tile
 NDMA = TILE // 4096                                  # direct-to-LDS loads per wavefront and tile (4 wavefronts x 1 KiB each)
 NSLOT = 4 * DB + 2 * KS                              # MFMAs per key block and wavefront
 SPLIT = 4 * 2 * TILE > 65536                         # ring beyond the 16-bit offset field: second set of base registers
-GAP = 8.0                                            # log2 units a block maximum may exceed the reference by
+                                                     # (GAP, log2 units a block maximum may exceed the reference by, arrives in s46)
 
 # ---- AGPRs
 def ACC(db, qb): return 16 * (2 * db + qb)
@@ -63,6 +63,7 @@ RT = 200                                             # 200..223: temporaries of 
 # inputs (pinned by the C++ side): v[224:239]
 I_QROW0, I_QROW1, I_XBASE, I_GF16, I_TRBASE, I_LF16, I_KOFF0, I_VOFF0, I_OOFF, I_LSEOFF = (
     224, 226, 228, 229, 230, 231, 232, 233, 234, 235)
+S_GAP = 46
 (S_LDS, S_WAVE, S_NT, S_KRS16, S_VRS16, S_SCALE, S_OPTR, S_OQB, S_TBL, S_KTILE, S_VTILE, S_LSEPTR) = (
     32, 33, 34, 35, 36, 37, 38, 40, 41, 42, 43, 44)
 # scalar temporaries
@@ -384,7 +385,7 @@ def generate():
     e.raw(f"v_mul_f32 {vr(TMP)}, {sr(S_SCALE)}, {vr(TMP)}")
     e.raw("s_nop 0")
     e.raw(f"v_readfirstlane_b32 {sr(S_CEXP)}, {vr(TMP)}")
-    e.raw(f"v_mov_b32 {vr(GAPR)}, {GAP}")
+    e.raw(f"v_mov_b32 {vr(GAPR)}, {sr(S_GAP)}")
     e.raw(f"v_mov_b32 {vr(KOFF)}, {vr(I_KOFF0)}")
     e.raw(f"v_mov_b32 {vr(VOFF)}, {vr(I_VOFF0)}")
     e.raw(f"v_mov_b32 {vr(OOFF)}, {vr(I_OOFF)}")

@@ -63,6 +63,7 @@ struct FwdArgs {
   // (floats); the states are combined afterwards.  0 or 1: one workgroup walks the whole table.
   int32_t n_split;
   int64_t split_o, split_l;
+  float gap;         // fast kernel: log2 units a block maximum may exceed the lazy exponent reference by (set by its launcher)
 };
 
 // table entries [lo, hi) of split y

@@ -12,7 +12,7 @@ CSRC = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
 
 # script, macro prefix, pinned input registers (VGPRs, SGPRs) handed over by the C++ shell
 GENERATORS = [
-    ("gen_fwd_asm.py", "ST_FWD_FAST", range(224, 240), range(32, 46)),
+    ("gen_fwd_asm.py", "ST_FWD_FAST", range(224, 240), range(32, 47)),
     ("gen_bwd_dq_asm.py", "ST_DQ_FAST", range(160, 180), range(32, 44)),
     ("gen_bwd_dkv_asm.py", "ST_DKV_FAST", range(176, 192), list(range(32, 47)) + list(range(48, 59))),
 ]

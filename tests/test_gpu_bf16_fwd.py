@@ -164,3 +164,29 @@ def test_many_chunks_forward_and_backward(case):
         assert_close(host(dv[j]), dv_ref[x], "bf16", f"dv {j}")
     for j in set(range(n)) - set(sub):
         assert float(dk[j].abs().max()) == 0.0 and float(dv[j].abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("gap", ["0", "0.5", "2"])
+@pytest.mark.parametrize("D", [128, 64])
+def test_forward_with_a_tight_exponent_reference(D, gap, monkeypatch):
+    """ST_FWD_GAP (a testing override of the hand-scheduled loop) lets a block maximum exceed the lazy exponent
+    reference by only `gap` log2 units, so the rescale routine runs in most blocks of the walk (both score
+    buffers, the last tile's blocks, several times per row) instead of a few times per kernel."""
+    monkeypatch.setenv("ST_FWD_GAP", gap)
+    w = si.Workload("fast_tight_reference", 87, "bf16", 1, 2, 1, D, 512, 192, 6, 6 * 192 - 512, True, False, k_ramp=0.4)
+    inp = si.make_inputs(w)
+    q, ks, vs, _ = upload(inp)
+    q_pos, k_pos = positions(w)
+    koffs = [w.k_offset(j) for j in range(w.n_chunks)]
+    o_ref, lse_ref = oa.attention_forward(inp.q, inp.k, inp.v, q_pos, k_pos, w.causal, w.scale)
+    for order in ([0, 1, 2, 3, 4, 5], [5, 2, 0, 4, 1, 3], [3]):
+        sub = sorted(order)
+        if len(order) < w.n_chunks:
+            o_r, l_r = oa.attention_forward(inp.q, [inp.k[j] for j in sub], [inp.v[j] for j in sub], q_pos,
+                                            [k_pos[j] for j in sub], w.causal, w.scale)
+        else:
+            o_r, l_r = o_ref, lse_ref
+        o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, st.ST_RING_FUSED)
+        torch.cuda.synchronize()
+        assert_close(host(o), o_r, "bf16", f"o, order {order}")
+        assert_close(host(lse), l_r, "bf16", f"lse, order {order}", lse=True)
