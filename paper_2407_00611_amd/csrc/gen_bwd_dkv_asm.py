@@ -88,7 +88,7 @@ STATS = 0                                            # stage s: nl[32] at 256 s,
 def QT(s): return 1024 + 2 * TQ * s
 def DOT(s): return 1024 + 2 * TQ * s + TQ
 VT = 1024 + 2 * TQ * NS                              # V tile of the workgroup: 256 rows
-LDS_BYTES = VT + 256 * ROW
+LDS_BYTES = max(VT + 256 * ROW, 4 * 2 * 32 * (4 * D + 16))   # the tiles of the loop; the epilogue's staging rows
 
 LAT = int(os.environ.get("ST_GEN_DKV_LAT", 3))          # MFMA slots between the issue of an LDS read and its first use
 BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6 if D == 128 else 11))       # issue units of side work per MFMA slot (an MFMA occupies the pipe for 8 quad-cycles)
@@ -354,6 +354,123 @@ def gen_step(e, pool, u, seq, reads, next_reads):
     assert vi[0] == len(valu), f"VALU work left over: {len(valu) - vi[0]}"
 
 
+class InFlight:
+    """Memory operations of one counter in issue order (they complete in that order): need(tag) emits the wait
+    that makes the tagged operation, and every older one, complete."""
+    def __init__(self, e, counter, limit):
+        self.e, self.counter, self.limit, self.q = e, counter, limit, []
+
+    def issue(self, text, tag):
+        if len(self.q) >= self.limit:                    # keep the hardware counter from saturating
+            self.q = self.q[len(self.q) - self.limit // 2:]
+            self.e.raw(f"s_waitcnt {self.counter}({len(self.q)})")
+        self.e.raw(text)
+        self.q.append(tag)
+
+    def need(self, tag):
+        if tag in self.q:
+            self.q = self.q[self.q.index(tag) + 1:]
+            assert len(self.q) <= (63 if self.counter == "vmcnt" else 15)
+            self.e.raw(f"s_waitcnt {self.counter}({len(self.q)})")
+
+
+def epilogue(e):
+    """dk_acc += scale * dK, dv_acc += dV.  The accumulators hold dK^T / dV^T with lane = key, so a lane owns
+    16-byte pieces of 32 different rows of the output: written like that, every access of a wavefront touches
+    32 cache lines and the epilogue is bound by the rate of cache-line lookups.  Each wavefront therefore turns
+    its tile through LDS (its own region, rows padded by 16 bytes) and reads, adds and writes the fp32
+    accumulators in HBM as whole rows: 64 lanes x 16 bytes = RPI complete rows per access.
+    Four passes (key block x {dK, dV}); the HBM reads run two passes ahead of their use, nothing waits for the
+    stores (vmcnt counts loads and stores in issue order)."""
+    RSL = 4 * D + 16                                   # bytes of a padded fp32 row in LDS
+    LPR = D // 4                                       # lanes per row
+    RPI = 64 // LPR                                    # rows per access
+    NLD = 32 // RPI                                    # accesses per pass
+    LG = LPR.bit_length() - 1
+    def G(p, n): return 4 * NLD * (p % 2) + 4 * n      # HBM values of pass p
+    def T(n): return 128 + 4 * n                       # the wavefront's own values, row layout
+    def W(k): return 192 + 4 * (k % 4)                 # accumulator pieces on their way to LDS
+    LR, LW, GOFF, LANE, TA, TB = 208, 209, 210, 211, 212, 213
+    PTL, PTS, STEP, SW = 64, 66, 68, 69                # scalar temporaries of the loop, free now
+    e.comment("---- epilogue: dk_acc += scale * dK, dv_acc += dV, through LDS so that HBM sees whole rows")
+    e.raw("s_nop 7")
+    e.raw("s_nop 7")
+    e.raw("s_barrier")                                 # every wavefront is done with the tiles in LDS
+    e.raw(f"v_mbcnt_lo_u32_b32 {vr(LANE)}, -1, 0")
+    e.raw(f"v_mbcnt_hi_u32_b32 {vr(LANE)}, -1, {vr(LANE)}")
+    e.raw(f"s_lshr_b32 {sr(STEP)}, {sr(S_RS32)}, 5")                     # bytes of one output row
+    e.raw(f"s_lshl_b32 {sr(SW)}, {sr(S_WAVE)}, 6")
+    e.raw(f"v_lshrrev_b32 {vr(TA)}, {LG}, {vr(LANE)}")                   # row of this lane within an access
+    e.raw(f"v_and_b32 {vr(TB)}, {LPR - 1}, {vr(LANE)}")
+    e.raw(f"v_lshlrev_b32 {vr(TB)}, 4, {vr(TB)}")                        # byte column of this lane
+    e.raw(f"v_add_u32 {vr(GOFF)}, {sr(SW)}, {vr(TA)}")
+    e.raw(f"v_mul_lo_u32 {vr(GOFF)}, {vr(GOFF)}, {sr(STEP)}")
+    e.raw(f"v_add_u32 {vr(GOFF)}, {vr(GOFF)}, {vr(TB)}")
+    e.raw(f"s_mul_i32 {sr(SW)}, {sr(S_WAVE)}, {2 * 32 * RSL}")
+    e.raw(f"s_add_u32 {sr(SW)}, {sr(SW)}, {sr(S_LDS)}")                  # LDS region of this wavefront (two passes)
+    e.raw(f"v_mul_u32_u24 {vr(TA)}, {RSL}, {vr(TA)}")
+    e.raw(f"v_add_u32 {vr(TA)}, {vr(TA)}, {vr(TB)}")
+    e.raw(f"v_add_u32 {vr(LR)}, {sr(SW)}, {vr(TA)}")
+    e.raw(f"v_and_b32 {vr(TA)}, 31, {vr(LANE)}")                         # key of this lane, half of the 32 bytes
+    e.raw(f"v_mul_u32_u24 {vr(TA)}, {RSL}, {vr(TA)}")
+    e.raw(f"v_lshrrev_b32 {vr(TB)}, 5, {vr(LANE)}")
+    e.raw(f"v_lshlrev_b32 {vr(TB)}, 4, {vr(TB)}")
+    e.raw(f"v_add_u32 {vr(TA)}, {vr(TA)}, {vr(TB)}")
+    e.raw(f"v_add_u32 {vr(LW)}, {sr(SW)}, {vr(TA)}")
+    e.raw(f"s_mul_i32 {sr(STEP)}, {sr(STEP)}, {RPI}")                    # bytes between two accesses
+
+    passes = [(nb, which) for nb in range(NKB) for which in ("k", "v")]
+    vm, lgkm = InFlight(e, "vmcnt", 1000), InFlight(e, "lgkmcnt", 12)
+
+    def pointer(ptr, p):
+        nb, which = passes[p]
+        e.raw(f"s_mov_b64 {sr(ptr, 2)}, {sr(S_DKPTR if which == 'k' else S_DVPTR, 2)}")
+        if nb:
+            e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(S_RS32)}")
+            e.raw(f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0")
+
+    def step(ptr):
+        e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(STEP)}")
+        e.raw(f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0")
+
+    def loads(p):
+        pointer(PTL, p)
+        for n in range(NLD):
+            vm.issue(f"global_load_dwordx4 {vr(G(p, n), 4)}, {vr(GOFF)}, {sr(PTL, 2)}", ("ld", p, n))
+            step(PTL)
+
+    loads(0)
+    loads(1)
+    for p, (nb, which) in enumerate(passes):
+        accf = ACC_K if which == "k" else ACC_V
+        region = 32 * RSL * (p % 2)
+        for k in range(4 * DB):
+            db, j = divmod(k, 4)
+            for i in range(4):
+                e.raw(f"v_accvgpr_read_b32 {vr(W(k) + i)}, {ar(accf(db, nb) + 4 * j + i)}")
+            e.raw("s_nop 0")
+            lgkm.issue(f"ds_write_b128 {vr(LW)}, {vr(W(k), 4)} offset:{region + 128 * db + 32 * j}", ("w", p, k))
+        ahead = min(8, NLD)
+        for n in range(ahead):
+            lgkm.issue(f"ds_read_b128 {vr(T(n), 4)}, {vr(LR)} offset:{region + n * RPI * RSL}", ("r", p, n))
+        pointer(PTS, p)
+        for n in range(NLD):
+            lgkm.need(("r", p, n))
+            vm.need(("ld", p, n))
+            for i in range(4):
+                if which == "k":
+                    e.raw(f"v_fma_f32 {vr(G(p, n) + i)}, {vr(T(n) + i)}, {sr(S_SCALE)}, {vr(G(p, n) + i)}")
+                else:
+                    e.raw(f"v_add_f32 {vr(G(p, n) + i)}, {vr(T(n) + i)}, {vr(G(p, n) + i)}")
+            if n + ahead < NLD:
+                m = n + ahead
+                lgkm.issue(f"ds_read_b128 {vr(T(m), 4)}, {vr(LR)} offset:{region + m * RPI * RSL}", ("r", p, m))
+            vm.issue(f"global_store_dwordx4 {vr(GOFF)}, {vr(G(p, n), 4)}, {sr(PTS, 2)}", ("st", p, n))
+            step(PTS)
+        if p + 2 < len(passes):                         # the registers just stored take the HBM values of a later pass
+            loads(p + 2)
+
+
 def generate():
     e = Emitter()
     pool = Pool()
@@ -470,33 +587,7 @@ def generate():
     e.raw(l_done + ":")
     e.raw("s_waitcnt vmcnt(0) lgkmcnt(0)")
 
-    e.comment("---- epilogue: dk_acc += scale * dK, dv_acc += dV; lane = key row, 4 consecutive d per 16-byte access")
-    e.raw("s_nop 7")
-    e.raw("s_nop 7")
-    for nb in range(NKB):
-        if nb == 1:
-            e.raw(f"v_add_u32 {vr(DKV_OFF)}, {sr(S_RS32)}, {vr(DKV_OFF)}")
-        for which, ptr, accf in (("k", S_DKPTR, ACC_K), ("v", S_DVPTR, ACC_V)):
-            for db in range(DB):
-                for j in range(4):
-                    t = S0 + 4 * (4 * db + j)
-                    e.raw(f"global_load_dwordx4 {vr(t, 4)}, {vr(DKV_OFF)}, {sr(ptr, 2)} offset:{128 * db + 32 * j}")
-            for db in range(DB):
-                for j in range(4):
-                    t = S0 + 4 * (4 * db + j)
-                    e.raw(f"s_waitcnt vmcnt({4 * DB - 1 - (4 * db + j)})")
-                    for i in range(4):
-                        e.raw(f"v_accvgpr_read_b32 {vr(TMP)}, {ar(accf(db, nb) + 4 * j + i)}")
-                        e.raw("s_nop 0")
-                        if which == "k":
-                            e.raw(f"v_fma_f32 {vr(t + i)}, {vr(TMP)}, {sr(S_SCALE)}, {vr(t + i)}")
-                        else:
-                            e.raw(f"v_add_f32 {vr(t + i)}, {vr(TMP)}, {vr(t + i)}")
-            for db in range(DB):
-                for j in range(4):
-                    t = S0 + 4 * (4 * db + j)
-                    e.raw(f"global_store_dwordx4 {vr(DKV_OFF)}, {vr(t, 4)}, {sr(ptr, 2)} offset:{128 * db + 32 * j}")
-            e.raw("s_waitcnt vmcnt(0)")
+    epilogue(e)
     return e
 
 
