@@ -442,12 +442,12 @@ int fwd_splits(const st_ring_desc* d, int n_visible) {
 //   forward, stepwise: partial O, partial lse, member O, member lse
 //   forward, fused:    partial O and partial lse, once (when more than one launch is needed) or once per
 //                      split of an under-filled launch: [O_0, lse_0, O_1, lse_1, ...]
-//   backward:          Delta
+//   backward:          Delta, then the tile counters of the dK/dV launch (kQueueInts ints)
 size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t backward) {
   if (d == nullptr) return 0;
   const size_t n_o = align_up((size_t)d->B * d->Sq * d->Hq * d->D * sizeof(float), 256);
   const size_t n_l = align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256);
-  if (backward) return n_l;
+  if (backward) return n_l + align_up(st::kQueueInts * sizeof(int32_t), 256);
   if (mode == ST_RING_STEPWISE) return 2 * (n_o + n_l);
   // the split grows with the number of visited chunks up to one launch's table, and any subset may be visited
   const int n_most = d->n_chunks < st::kMaxTable ? d->n_chunks : st::kMaxTable;
@@ -607,6 +607,7 @@ st_status st_ring_bwd(const st_ring_desc* d, const st_tensor* q, const st_tensor
   a.d_o = view_of(d_o);
   set_table_strides(a.t, d);
   a.lse = lse_final; a.delta = delta; a.dq = dq_acc;
+  a.queue = (int32_t*)((char*)workspace + align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256));
   const int per_launch = mode == ST_RING_FUSED ? st::kMaxTable : 1;
   for (int x0 = 0; x0 < n; x0 += per_launch) {
     const int cnt = n - x0 < per_launch ? n - x0 : per_launch;

@@ -84,7 +84,10 @@ struct BwdArgs {
   float* dv[kMaxTable];
   int32_t dkv_fast;    // 1: the fast dK/dV kernel runs too and owns the blocks dkv_fast_first_block describes
   int32_t dq_fast;     // 1: the fast dQ kernel runs too and owns the tiles dq_fast_tiles describes
+  int32_t* queue;      // nullable, kQueueInts ints of device memory: the fast dK/dV kernel hands its key tiles out
+                       // through it (one counter per XCD), so that XCDs that run faster take more of them
 };
+constexpr int kQueueInts = 8 * 32;   // 8 counters, 128 bytes apart
 
 // n partial states of the same query rows (each O fp32 [B,Sq_in,Hq,D], lse fp32 [B,Hq,Sq_in]) and the run of
 // rows [row0, row0 + Sq_out) the combined state keeps.

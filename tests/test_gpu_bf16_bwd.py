@@ -129,6 +129,22 @@ def test_backward_is_bit_reproducible():
     _ring_fwd_bwd(w, [3, 1, 0, 2], [0, 1, 0, 1], st.ST_RING_FUSED)
 
 
+@pytest.mark.parametrize("D", [128, 64])
+def test_dkv_tiles_through_the_queue(D):
+    """513 full key tiles (57 chunks x 9 KV heads, one 256-key tile each): at two tiles per CU and more the fused
+    dK/dV launch keeps one workgroup per CU and hands the tiles out through per-XCD counters; 513 is not a
+    multiple of 8, so the last XCD's range is short and its workgroups take tiles of the others.  Which workgroup
+    computes a tile does not change its arithmetic: two runs agree bit for bit."""
+    n = 57
+    w = si.Workload(f"dkv_queue_d{D}", 99, "bf16", 1, 9, 9, D, 96, 256, n, n * 256 - 96, True, True)
+    order = list(range(n - 1, -1, -1))
+    print(f"[dkv queue D={D}] {n} chunks x 9 heads", flush=True)
+    a = _ring_fwd_bwd(w, order, None, st.ST_RING_FUSED)
+    b = _ring_fwd_bwd(w, order, None, st.ST_RING_FUSED)
+    for j in range(n):
+        assert torch.equal(a[1][j], b[1][j]) and torch.equal(a[2][j], b[2][j])
+
+
 BHSD_CASES = [
     # a chunk table of the maximum length (64 entries) of 64-key chunks: forward and dQ loops
     si.Workload("fast_bhsd_64chunks", 97, "bf16", 2, 4, 2, 128, 288, 64, 64, 64 * 64 - 288, True, True),
