@@ -1,5 +1,7 @@
 """GPU parity, bf16 backward (MFMA path) against the fp64 oracle on the bf16-rounded inputs.
 Tolerance: max abs 2e-2 and relative Frobenius 1e-2 per tensor."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -134,15 +136,21 @@ def test_dkv_tiles_through_the_queue(D):
     """513 full key tiles (57 chunks x 9 KV heads, one 256-key tile each): at two tiles per CU and more the fused
     dK/dV launch keeps one workgroup per CU and hands the tiles out through per-XCD counters; 513 is not a
     multiple of 8, so the last XCD's range is short and its workgroups take tiles of the others.  Which workgroup
-    computes a tile does not change its arithmetic: two runs agree bit for bit."""
+    computes a tile does not change its arithmetic: two runs, and a run without the queue, agree bit for bit."""
     n = 57
     w = si.Workload(f"dkv_queue_d{D}", 99, "bf16", 1, 9, 9, D, 96, 256, n, n * 256 - 96, True, True)
     order = list(range(n - 1, -1, -1))
     print(f"[dkv queue D={D}] {n} chunks x 9 heads", flush=True)
     a = _ring_fwd_bwd(w, order, None, st.ST_RING_FUSED)
     b = _ring_fwd_bwd(w, order, None, st.ST_RING_FUSED)
+    os.environ["ST_DKV_QUEUE"] = "0"                 # every tile a workgroup of its own
+    try:
+        c = _ring_fwd_bwd(w, order, None, st.ST_RING_FUSED)
+    finally:
+        del os.environ["ST_DKV_QUEUE"]
     for j in range(n):
         assert torch.equal(a[1][j], b[1][j]) and torch.equal(a[2][j], b[2][j])
+        assert torch.equal(a[1][j], c[1][j]) and torch.equal(a[2][j], c[2][j])
 
 
 BHSD_CASES = [
