@@ -152,7 +152,7 @@ st_status st_attn_delta(const st_block_desc* desc, const st_tensor* d_o, const s
  *   dq_acc fp32 [B,Sq,Hq,D]   ACCUMULATED (+=): the circulating query gradient
  *   dk_acc, dv_acc fp32 [B,Sk,Hkv,D] ACCUMULATED (+=): stay with the chunk
  * The caller zeroes the accumulators once.  Every accumulator element is owned by one workgroup per
- * launch (read, add, write; no atomics), so results are bit-reproducible; calls that add into the same
+ * launch (read, add, write; no atomic adds), so results are bit-reproducible; calls that add into the same
  * accumulator must be ordered on one stream. */
 st_status st_attn_block_bwd(const st_block_desc* desc, const st_tensor* q, const st_tensor* k,
                             const st_tensor* v, const st_tensor* d_o, const float* lse_final,
@@ -218,7 +218,9 @@ st_status st_schedule_report(int32_t P, int32_t C, int64_t B, int64_t N, int64_t
  *   of the shard are skipped.
  * Forward outputs: o_acc fp32 [B,Sq,Hq,D], lse fp32 [B,Hq,Sq] (overwritten); o_lowp nullable,
  *   [B,Sq,Hq,D] in desc->dtype.
- * workspace: device, >= st_ring_workspace_bytes(desc, mode, backward) bytes, 256-byte aligned. */
+ * workspace: device, >= st_ring_workspace_bytes(desc, mode, backward) bytes, 256-byte aligned.  Its contents
+ *   are the library's (partial states, Delta, the tile counters of the dK/dV launch) and mean nothing between
+ *   calls; calls that share a workspace must be ordered on one stream. */
 size_t st_ring_workspace_bytes(const st_ring_desc* desc, int32_t mode, int32_t backward);
 
 st_status st_ring_fwd(const st_ring_desc* desc, const st_tensor* q, const int32_t* order,
