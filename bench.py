@@ -3,8 +3,8 @@
 
 A step = one pass of the whole hot path over the workload, with all inputs resident in HBM:
   visit order -> ring forward (all chunks, online-softmax state, O in fp32 and bf16, lse)
-  -> zero the gradient accumulators -> Delta -> ring backward (dK/dV and dQ kernels)
-  -> fp32 -> bf16 casts of dQ, dK, dV.
+  -> zero the dQ accumulator -> Delta -> ring backward (dK/dV and dQ kernels; this visit being the chunks' only
+  one, dK / dV are assigned in fp32 and rounded to bf16 by the kernels that produce them) -> fp32 -> bf16 cast of dQ.
 The workload is benchmark configuration 4 (GQA 32/8 heads, D=128, Q shard 4096, 32 chunks of
 4096 keys, causal, last rank of a P=32 / C=4 concentric layout) with synthetic N(0,1) bf16 data.
 
@@ -179,6 +179,8 @@ def main() -> int:
         dv = [dkv[1, j] for j in range(w.n_chunks)]
         dq_low = torch.empty_like(o_low)
         dkv_low = torch.empty(dkv.shape, dtype=q.dtype, device=dev)
+        dk_low = [dkv_low[0, j] for j in range(w.n_chunks)]
+        dv_low = [dkv_low[1, j] for j in range(w.n_chunks)]
 
     if team:
         # what the team hands over: the other members' partial states of the same rows (computed here, untimed,
@@ -211,25 +213,25 @@ def main() -> int:
                            o_out_lowp=o_own_low)
         if w.backward:
             dq.zero_()
-            for j in order:
-                dkv[:, j].zero_()
-            st.st_ring_bwd(q, ks, vs, d_o, o_team_low, lse_team, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
-                           mode, workspace=ws_b)
+            st.st_ring_bwd_last(q, ks, vs, d_o, o_team_low, lse_team, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
+                                assign=True, dk_lowp=dk_low, dv_lowp=dv_low, mode=mode, workspace=ws_b)
             st.st_cast_from_f32(dq, storage, dq_low)
-            for j in order:
-                st.st_cast_from_f32(dkv[0, j], storage, dkv_low[0, j])
-                st.st_cast_from_f32(dkv[1, j], storage, dkv_low[1, j])
 
     def step_ring():
         st.st_ring_fwd(q, ks, vs, w.q_where, koffs, w.causal, w.scale, order, members, mode,
                        o_acc=o_acc, lse=lse, o_lowp=o_low, workspace=ws_f)
         if w.backward:
             dq.zero_()
-            dkv.zero_()
-            st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
-                           mode, workspace=ws_b)
+            if bf16:
+                # this visit is the chunks' only one: dK / dV are assigned and rounded by the kernels that produce them
+                st.st_ring_bwd_last(q, ks, vs, d_o, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
+                                    assign=True, dk_lowp=dk_low, dv_lowp=dv_low, mode=mode, workspace=ws_b)
+            else:
+                dkv.zero_()
+                st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq, dk, dv,
+                               mode, workspace=ws_b)
+                st.st_cast_from_f32(dkv, storage, dkv_low)
             st.st_cast_from_f32(dq, storage, dq_low)
-            st.st_cast_from_f32(dkv, storage, dkv_low)
 
     step = step_team if team else step_ring
 

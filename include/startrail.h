@@ -237,6 +237,24 @@ st_status st_ring_bwd(const st_ring_desc* desc, const st_tensor* q, const st_ten
                       float* dq_acc, float* const* dk_acc, float* const* dv_acc,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* st_ring_bwd for the LAST visit of the listed chunks, with the work that follows a chunk's last visit folded
+ * into the kernels that produce dK / dV (Section 3.2 "Backward Propagation": the key and value gradients are
+ * complete once the chunk has met every query shard).
+ *   kv_flags   ST_KV_ASSIGN: dk_acc[j], dv_acc[j] of every chunk in `order` are OVERWRITTEN with this call's
+ *              contribution instead of added to (they need not be zeroed; a listed chunk that lies entirely in
+ *              the shard's causal future is set to zero).  0: accumulate, as st_ring_bwd.
+ *   dk_lowp, dv_lowp  nullable; host arrays [n_chunks] of device pointers, entries nullable (both or neither of a
+ *              chunk): the final dk_acc[j] / dv_acc[j] rounded to desc->dtype, dense [B,Sk,Hkv,D], 16-byte
+ *              aligned.  ST_BF16 descriptors only.
+ * dq_acc is accumulated as in st_ring_bwd.  Same workspace. */
+enum { ST_KV_ASSIGN = 1 };
+st_status st_ring_bwd_last(const st_ring_desc* desc, const st_tensor* q, const st_tensor* d_o,
+                           const st_tensor* o, int32_t o_dtype, const float* lse_final,
+                           const int32_t* order, int32_t n_visit, int32_t mode,
+                           float* dq_acc, float* const* dk_acc, float* const* dv_acc,
+                           int32_t kv_flags, void* const* dk_lowp, void* const* dv_lowp,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---- per-kernel timing for benchmarks (not part of the method) ----
  * Between st_profile_begin() and st_profile_end() the library records a HIP event on the launch
  * stream before and after every kernel it launches (this creates hipEvent_t objects; at most 4096

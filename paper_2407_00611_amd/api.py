@@ -14,6 +14,7 @@ import torch
 
 ST_F32, ST_BF16 = 0, 1
 ST_RING_STEPWISE, ST_RING_FUSED = 0, 1
+ST_KV_ASSIGN = 1
 ST_MAX_CHUNKS = 256
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libstartrail.so")
@@ -84,6 +85,9 @@ def _load() -> C.CDLL:
         "st_ring_fwd": (C.c_int, [R, T, i32p, i32p, C.c_int32, C.c_int32, f32p, f32p, vp, vp, C.c_size_t, vp]),
         "st_ring_bwd": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
+        "st_ring_bwd_last": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
+                                       C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
+                                       C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
         "st_profile_begin": (C.c_int, []),
         "st_profile_end": (C.c_int, [C.POINTER(st_profile_entry), C.c_int32, C.POINTER(C.c_int32)]),
         "st_status_str": (C.c_char_p, [C.c_int]),
@@ -98,7 +102,7 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_combine", "st_attn_delta", "st_attn_block_bwd", "st_cast_from_f32",
-           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_profile_begin",
+           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_last", "st_profile_begin",
            "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
@@ -378,3 +382,46 @@ def st_ring_bwd(q, k_chunks, v_chunks, d_o, o, lse_final, q_offset: int, k_offse
                             _i32_array(order), len(order), mode, _ptr(dq_acc),
                             C.cast(dk_ptr, C.POINTER(C.c_void_p)), C.cast(dv_ptr, C.POINTER(C.c_void_p)),
                             C.c_void_p(ws_ptr), ws_bytes, _stream(stream)), "st_ring_bwd")
+
+
+def st_ring_bwd_last(q, k_chunks, v_chunks, d_o, o, lse_final, q_offset: int, k_offsets: Sequence[int], causal: bool,
+                     scale: float, order: Sequence[int], dq_acc, dk_acc: Sequence[Optional[torch.Tensor]],
+                     dv_acc: Sequence[Optional[torch.Tensor]], assign: bool = False,
+                     dk_lowp: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                     dv_lowp: Optional[Sequence[Optional[torch.Tensor]]] = None, mode: int = ST_RING_FUSED,
+                     workspace=None, stream=None) -> None:
+    B, Sq, Hq, D = q.shape
+    r = _Ring(q, k_chunks, v_chunks, q_offset, k_offsets, causal, scale)
+    n = len(k_chunks)
+    _f32_dense(dq_acc, (B, Sq, Hq, D), "dq_acc"); _f32_dense(lse_final, (B, Hq, Sq), "lse_final")
+    kv_shape = tuple(k_chunks[0].shape)
+    for t in list(dk_acc) + list(dv_acc):
+        if t is not None:
+            _f32_dense(t, kv_shape, "dk_acc/dv_acc entry")
+
+    def table(ts):
+        if ts is None:
+            return None
+        for t in ts:
+            if t is not None and not (t.is_cuda and t.is_contiguous() and t.dtype == q.dtype and tuple(t.shape) == kv_shape):
+                raise ValueError("dk_lowp/dv_lowp entry: expected a dense device tensor shaped like a chunk, in the dtype of q")
+        return (C.c_void_p * n)(*[(t.data_ptr() if t is not None else None) for t in ts])
+
+    dk_ptr, dv_ptr = _ptr_table(dk_acc, n), _ptr_table(dv_acc, n)
+    lk, lv = table(dk_lowp), table(dv_lowp)
+    need = int(_lib.st_ring_workspace_bytes(C.byref(r.desc), mode, 1))
+    if workspace is None:
+        workspace = torch.empty(need + 256, dtype=torch.uint8, device=q.device)
+    ws_ptr = (workspace.data_ptr() + 255) // 256 * 256
+    ws_bytes = workspace.numel() * workspace.element_size() - (ws_ptr - workspace.data_ptr())
+    tq, td, to = _view(q), _view(d_o), _view(o)
+    vpp = C.POINTER(C.c_void_p)
+    _check(_lib.st_ring_bwd_last(C.byref(r.desc), C.byref(tq), C.byref(td), C.byref(to), _dtype_code(o), _ptr(lse_final),
+                                 _i32_array(order), len(order), mode, _ptr(dq_acc), C.cast(dk_ptr, vpp), C.cast(dv_ptr, vpp),
+                                 ST_KV_ASSIGN if assign else 0, C.cast(lk, vpp) if lk is not None else None,
+                                 C.cast(lv, vpp) if lv is not None else None,
+                                 C.c_void_p(ws_ptr), ws_bytes, _stream(stream)), "st_ring_bwd_last")
+
+
+def _ptr_table(ts, n):
+    return (C.c_void_p * n)(*[(t.data_ptr() if t is not None else None) for t in ts])

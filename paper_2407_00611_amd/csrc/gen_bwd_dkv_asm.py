@@ -75,6 +75,7 @@ IN_SA, IN_SB = 32, 48                                # s[32:47], s[48:63]
 S_QPTR, S_DOPTR, S_LSEPTR, S_DLPTR = 32, 34, 36, 38
 S_QBS, S_QHS, S_DOBS, S_DOHS, S_STATHS, S_NBLK, S_NSTEPS, S_CEXP = 40, 41, 42, 43, 44, 45, 46, 47
 S_VPTR, S_VRS16, S_LDS, S_DKPTR, S_DVPTR, S_WAVE, S_RS32, S_SCALE = 48, 50, 51, 52, 54, 56, 57, 58
+S_FLAGS, S_DKLP, S_DVLP = 59, 60, 62                # epilogue variant; bf16 copies of the dK / dV tile (if asked for)
 # scalar temporaries (clobbered)
 T_QPTR, T_QHEAD, T_DOPTR, T_DOHEAD = 64, 66, 68, 70
 T_LSEPTR, T_LSEHEAD, T_DLPTR, T_DLHEAD = 72, 74, 76, 78
@@ -375,24 +376,26 @@ class InFlight:
 
 
 def epilogue(e):
-    """dk_acc += scale * dK, dv_acc += dV.  The accumulators hold dK^T / dV^T with lane = key, so a lane owns
+    """dk_acc (+)= scale * dK, dv_acc (+)= dV.  The accumulators hold dK^T / dV^T with lane = key, so a lane owns
     16-byte pieces of 32 different rows of the output: written like that, every access of a wavefront touches
     32 cache lines and the epilogue is bound by the rate of cache-line lookups.  Each wavefront therefore turns
     its tile through LDS (its own region, rows padded by 16 bytes) and reads, adds and writes the fp32
     accumulators in HBM as whole rows: 64 lanes x 16 bytes = RPI complete rows per access.
-    Four passes (key block x {dK, dV}); the HBM reads run two passes ahead of their use, nothing waits for the
-    stores (vmcnt counts loads and stores in issue order)."""
+    Four passes (key block x {dK, dV}).  Four variants, chosen by S_FLAGS: bit 0 = the accumulators are assigned,
+    not added to (nothing is read from HBM); bit 1 = the final values are also written rounded to bf16.  When
+    adding, the HBM reads run two passes ahead of their use; nothing waits for the stores (vmcnt counts loads
+    and stores in issue order, which is why every variant has its own waits)."""
     RSL = 4 * D + 16                                   # bytes of a padded fp32 row in LDS
     LPR = D // 4                                       # lanes per row
     RPI = 64 // LPR                                    # rows per access
     NLD = 32 // RPI                                    # accesses per pass
     LG = LPR.bit_length() - 1
-    def G(p, n): return 4 * NLD * (p % 2) + 4 * n      # HBM values of pass p
+    def G(p, n): return 4 * NLD * (p % 2) + 4 * n      # HBM values of pass p (two sets)
     def T(n): return 128 + 4 * n                       # the wavefront's own values, row layout
-    def W(k): return 192 + 4 * (k % 4)                 # accumulator pieces on their way to LDS
-    LR, LW, GOFF, LANE, TA, TB = 208, 209, 210, 211, 212, 213
-    PTL, PTS, STEP, SW = 64, 66, 68, 69                # scalar temporaries of the loop, free now
-    e.comment("---- epilogue: dk_acc += scale * dK, dv_acc += dV, through LDS so that HBM sees whole rows")
+    def W(k): return 192 + 4 * (k % 4)                 # accumulator pieces on their way to LDS; later bf16 pairs
+    LR, LW, GOFF, LANE, TA, TB, GOFF2 = 208, 209, 210, 211, 212, 213, 214
+    PTL, PTS, STEP, SW, PTB, STEP2 = 64, 66, 68, 69, 70, 72   # scalar temporaries of the loop, free now
+    e.comment("---- epilogue: dk_acc (+)= scale * dK, dv_acc (+)= dV, through LDS so that HBM sees whole rows")
     e.raw("s_nop 7")
     e.raw("s_nop 7")
     e.raw("s_barrier")                                 # every wavefront is done with the tiles in LDS
@@ -406,6 +409,7 @@ def epilogue(e):
     e.raw(f"v_add_u32 {vr(GOFF)}, {sr(SW)}, {vr(TA)}")
     e.raw(f"v_mul_lo_u32 {vr(GOFF)}, {vr(GOFF)}, {sr(STEP)}")
     e.raw(f"v_add_u32 {vr(GOFF)}, {vr(GOFF)}, {vr(TB)}")
+    e.raw(f"v_lshrrev_b32 {vr(GOFF2)}, 1, {vr(GOFF)}")                   # the same in the bf16 copy
     e.raw(f"s_mul_i32 {sr(SW)}, {sr(S_WAVE)}, {2 * 32 * RSL}")
     e.raw(f"s_add_u32 {sr(SW)}, {sr(SW)}, {sr(S_LDS)}")                  # LDS region of this wavefront (two passes)
     e.raw(f"v_mul_u32_u24 {vr(TA)}, {RSL}, {vr(TA)}")
@@ -418,57 +422,92 @@ def epilogue(e):
     e.raw(f"v_add_u32 {vr(TA)}, {vr(TA)}, {vr(TB)}")
     e.raw(f"v_add_u32 {vr(LW)}, {sr(SW)}, {vr(TA)}")
     e.raw(f"s_mul_i32 {sr(STEP)}, {sr(STEP)}, {RPI}")                    # bytes between two accesses
+    e.raw(f"s_lshr_b32 {sr(STEP2)}, {sr(STEP)}, 1")
 
     passes = [(nb, which) for nb in range(NKB) for which in ("k", "v")]
-    vm, lgkm = InFlight(e, "vmcnt", 1000), InFlight(e, "lgkmcnt", 12)
+    l_var = [e.label(f"epi{v}") for v in range(4)]
+    l_end = e.label("epi_end")
+    for v in (1, 2, 3):
+        e.raw(f"s_cmp_eq_u32 {sr(S_FLAGS)}, {v}")
+        e.raw(f"s_cbranch_scc1 {l_var[v]}")
 
-    def pointer(ptr, p):
-        nb, which = passes[p]
-        e.raw(f"s_mov_b64 {sr(ptr, 2)}, {sr(S_DKPTR if which == 'k' else S_DVPTR, 2)}")
-        if nb:
-            e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(S_RS32)}")
+    def body(assign, lowp):
+        vm, lgkm = InFlight(e, "vmcnt", 1000), InFlight(e, "lgkmcnt", 12)
+
+        def pointer(ptr, p, bf16=False):
+            nb, which = passes[p]
+            base = (S_DKLP if which == "k" else S_DVLP) if bf16 else (S_DKPTR if which == "k" else S_DVPTR)
+            e.raw(f"s_mov_b64 {sr(ptr, 2)}, {sr(base, 2)}")
+            if nb:
+                if bf16:
+                    e.raw(f"s_lshr_b32 {sr(SW)}, {sr(S_RS32)}, 1")
+                e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(SW if bf16 else S_RS32)}")
+                e.raw(f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0")
+
+        def step(ptr, by=STEP):
+            e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(by)}")
             e.raw(f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0")
 
-    def step(ptr):
-        e.raw(f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(STEP)}")
-        e.raw(f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0")
+        def loads(p):
+            pointer(PTL, p)
+            for n in range(NLD):
+                vm.issue(f"global_load_dwordx4 {vr(G(p, n), 4)}, {vr(GOFF)}, {sr(PTL, 2)}", ("ld", p, n))
+                step(PTL)
 
-    def loads(p):
-        pointer(PTL, p)
-        for n in range(NLD):
-            vm.issue(f"global_load_dwordx4 {vr(G(p, n), 4)}, {vr(GOFF)}, {sr(PTL, 2)}", ("ld", p, n))
-            step(PTL)
-
-    loads(0)
-    loads(1)
-    for p, (nb, which) in enumerate(passes):
-        accf = ACC_K if which == "k" else ACC_V
-        region = 32 * RSL * (p % 2)
-        for k in range(4 * DB):
-            db, j = divmod(k, 4)
-            for i in range(4):
-                e.raw(f"v_accvgpr_read_b32 {vr(W(k) + i)}, {ar(accf(db, nb) + 4 * j + i)}")
-            e.raw("s_nop 0")
-            lgkm.issue(f"ds_write_b128 {vr(LW)}, {vr(W(k), 4)} offset:{region + 128 * db + 32 * j}", ("w", p, k))
-        ahead = min(8, NLD)
-        for n in range(ahead):
-            lgkm.issue(f"ds_read_b128 {vr(T(n), 4)}, {vr(LR)} offset:{region + n * RPI * RSL}", ("r", p, n))
-        pointer(PTS, p)
-        for n in range(NLD):
-            lgkm.need(("r", p, n))
-            vm.need(("ld", p, n))
-            for i in range(4):
-                if which == "k":
-                    e.raw(f"v_fma_f32 {vr(G(p, n) + i)}, {vr(T(n) + i)}, {sr(S_SCALE)}, {vr(G(p, n) + i)}")
+        deep = 1 if lowp else 2                         # passes the HBM reads run ahead (the wait counter holds 63)
+        if not assign:
+            for p in range(deep):
+                loads(p)
+        for p, (nb, which) in enumerate(passes):
+            accf = ACC_K if which == "k" else ACC_V
+            region = 32 * RSL * (p % 2)
+            for k in range(4 * DB):
+                db, j = divmod(k, 4)
+                for i in range(4):
+                    e.raw(f"v_accvgpr_read_b32 {vr(W(k) + i)}, {ar(accf(db, nb) + 4 * j + i)}")
+                e.raw("s_nop 0")
+                lgkm.issue(f"ds_write_b128 {vr(LW)}, {vr(W(k), 4)} offset:{region + 128 * db + 32 * j}", ("w", p, k))
+            ahead = min(8, NLD)
+            for n in range(ahead):
+                lgkm.issue(f"ds_read_b128 {vr(T(n), 4)}, {vr(LR)} offset:{region + n * RPI * RSL}", ("r", p, n))
+            pointer(PTS, p)
+            if lowp:
+                pointer(PTB, p, bf16=True)
+            for n in range(NLD):
+                lgkm.need(("r", p, n))
+                if assign:
+                    res = T(n)                          # the value itself is the result
+                    if which == "k":
+                        for i in range(4):
+                            e.raw(f"v_mul_f32 {vr(res + i)}, {sr(S_SCALE)}, {vr(res + i)}")
                 else:
-                    e.raw(f"v_add_f32 {vr(G(p, n) + i)}, {vr(T(n) + i)}, {vr(G(p, n) + i)}")
-            if n + ahead < NLD:
-                m = n + ahead
-                lgkm.issue(f"ds_read_b128 {vr(T(m), 4)}, {vr(LR)} offset:{region + m * RPI * RSL}", ("r", p, m))
-            vm.issue(f"global_store_dwordx4 {vr(GOFF)}, {vr(G(p, n), 4)}, {sr(PTS, 2)}", ("st", p, n))
-            step(PTS)
-        if p + 2 < len(passes):                         # the registers just stored take the HBM values of a later pass
-            loads(p + 2)
+                    res = G(p, n)
+                    vm.need(("ld", p, n))
+                    for i in range(4):
+                        if which == "k":
+                            e.raw(f"v_fma_f32 {vr(res + i)}, {vr(T(n) + i)}, {sr(S_SCALE)}, {vr(res + i)}")
+                        else:
+                            e.raw(f"v_add_f32 {vr(res + i)}, {vr(T(n) + i)}, {vr(res + i)}")
+                if n + ahead < NLD:
+                    m = n + ahead
+                    lgkm.issue(f"ds_read_b128 {vr(T(m), 4)}, {vr(LR)} offset:{region + m * RPI * RSL}", ("r", p, m))
+                vm.issue(f"global_store_dwordx4 {vr(GOFF)}, {vr(res, 4)}, {sr(PTS, 2)}", ("st", p, n))
+                step(PTS)
+                if lowp:
+                    lo = 192 + 2 * (n % 8)
+                    e.raw(f"v_cvt_pk_bf16_f32 {vr(lo)}, {vr(res)}, {vr(res + 1)}")
+                    e.raw(f"v_cvt_pk_bf16_f32 {vr(lo + 1)}, {vr(res + 2)}, {vr(res + 3)}")
+                    vm.issue(f"global_store_dwordx2 {vr(GOFF2)}, {vr(lo, 2)}, {sr(PTB, 2)}", ("sb", p, n))
+                    step(PTB, STEP2)
+            if not assign and p + deep < len(passes):   # the registers just stored take the HBM values of a later pass
+                loads(p + deep)
+
+    for v in range(4):
+        e.raw(l_var[v] + ":")
+        body(assign=bool(v & 1), lowp=bool(v & 2))
+        if v < 3:
+            e.raw(f"s_branch {l_end}")
+    e.raw(l_end + ":")
 
 
 def generate():

@@ -574,6 +574,15 @@ st_status st_ring_bwd(const st_ring_desc* d, const st_tensor* q, const st_tensor
                       int32_t o_dtype, const float* lse_final, const int32_t* order, int32_t n_visit, int32_t mode,
                       float* dq_acc, float* const* dk_acc, float* const* dv_acc, void* workspace,
                       size_t workspace_bytes, void* hip_stream) {
+  return st_ring_bwd_last(d, q, d_o, o, o_dtype, lse_final, order, n_visit, mode, dq_acc, dk_acc, dv_acc, 0, nullptr,
+                          nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+st_status st_ring_bwd_last(const st_ring_desc* d, const st_tensor* q, const st_tensor* d_o, const st_tensor* o,
+                           int32_t o_dtype, const float* lse_final, const int32_t* order, int32_t n_visit,
+                           int32_t mode, float* dq_acc, float* const* dk_acc, float* const* dv_acc, int32_t kv_flags,
+                           void* const* dk_lowp, void* const* dv_lowp, void* workspace, size_t workspace_bytes,
+                           void* hip_stream) {
   ST_TRY(check_ring(d, q, order, n_visit));
   if (mode != ST_RING_STEPWISE && mode != ST_RING_FUSED) return fail(ST_ERR_INVALID_ARG, "unknown mode %d", mode);
   if (o_dtype != ST_F32 && o_dtype != d->dtype) return fail(ST_ERR_INVALID_ARG, "o_dtype must be ST_F32 or the storage dtype");
@@ -583,19 +592,48 @@ st_status st_ring_bwd(const st_ring_desc* d, const st_tensor* q, const st_tensor
   ST_TRY(check_f32("lse_final", lse_final, n_o));
   ST_TRY(check_f32("dq_acc", dq_acc, n_o));
   if (n_visit > 0 && (!dk_acc || !dv_acc)) return fail(ST_ERR_INVALID_ARG, "null gradient tables");
-  if (n_o == 0) return ST_OK;
-  if (workspace == nullptr || workspace_bytes < st_ring_workspace_bytes(d, mode, 1)) return fail(ST_ERR_WORKSPACE, "backward workspace needs %zu bytes", st_ring_workspace_bytes(d, mode, 1));
-  if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(ST_ERR_ALIGNMENT, "workspace: not 256-byte aligned");
+  if (kv_flags & ~ST_KV_ASSIGN) return fail(ST_ERR_INVALID_ARG, "unknown kv_flags %d", kv_flags);
+  if ((dk_lowp == nullptr) != (dv_lowp == nullptr)) return fail(ST_ERR_INVALID_ARG, "dk_lowp and dv_lowp: both or neither");
+  if (dk_lowp && d->dtype != ST_BF16) return fail(ST_ERR_UNSUPPORTED, "bf16 copies of dK / dV need an ST_BF16 descriptor");
+  const bool assign = (kv_flags & ST_KV_ASSIGN) != 0;
+  const bool no_rows = n_o == 0;                     // no query rows: every contribution is zero
+  if (no_rows && !assign && !dk_lowp) return ST_OK;
+  if (!no_rows) {
+    if (workspace == nullptr || workspace_bytes < st_ring_workspace_bytes(d, mode, 1)) return fail(ST_ERR_WORKSPACE, "backward workspace needs %zu bytes", st_ring_workspace_bytes(d, mode, 1));
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(ST_ERR_ALIGNMENT, "workspace: not 256-byte aligned");
+  }
   hipStream_t stream = (hipStream_t)hip_stream;
+  auto unseen = [&](int j) { return no_rows || chunk_invisible(d, j); };
 
   int vis[ST_MAX_CHUNKS], n = 0;
-  for (int x = 0; x < n_visit; ++x)
-    if (!chunk_invisible(d, order[x])) {
-      const int j = order[x];
+  for (int x = 0; x < n_visit; ++x) {
+    const int j = order[x];
+    void* lk = dk_lowp ? dk_lowp[j] : nullptr;
+    void* lv = dk_lowp ? dv_lowp[j] : nullptr;
+    if ((lk == nullptr) != (lv == nullptr)) return fail(ST_ERR_INVALID_ARG, "dk_lowp[%d] and dv_lowp[%d]: both or neither", j, j);
+    if (lk && (reinterpret_cast<uintptr_t>(lk) % 16 || reinterpret_cast<uintptr_t>(lv) % 16))
+      return fail(ST_ERR_ALIGNMENT, "dk_lowp[%d] / dv_lowp[%d]: not 16-byte aligned", j, j);
+    const bool hidden = unseen(j);
+    if (!hidden || assign || lk) {
       ST_TRY(check_f32("dk_acc[j]", dk_acc[j], n_kv));
       ST_TRY(check_f32("dv_acc[j]", dv_acc[j], n_kv));
-      vis[n++] = j;
     }
+    if (!hidden) vis[n++] = j;
+  }
+  // a listed chunk nobody sees: its contribution is zero
+  for (int x = 0; x < n_visit; ++x) {
+    const int j = order[x];
+    if (!unseen(j) || n_kv == 0) continue;
+    if (assign) {
+      ST_HIP(st::launch_zero(dk_acc[j], n_kv * (int64_t)sizeof(float), stream), "dk_acc fill");
+      ST_HIP(st::launch_zero(dv_acc[j], n_kv * (int64_t)sizeof(float), stream), "dv_acc fill");
+    }
+    if (dk_lowp && dk_lowp[j]) {
+      ST_HIP(st::launch_cast(dk_acc[j], dk_lowp[j], n_kv, d->dtype, stream), "dk cast");
+      ST_HIP(st::launch_cast(dv_acc[j], dv_lowp[j], n_kv, d->dtype, stream), "dv cast");
+    }
+  }
+  if (no_rows) return ST_OK;
 
   float* delta = (float*)workspace;
   ST_HIP(st::launch_delta(view_of(d_o), d->dtype, view_of(o), o_dtype, delta, d->B, d->Sq, d->Hq, d->D, stream), "delta launch");
@@ -616,7 +654,15 @@ st_status st_ring_bwd(const st_ring_desc* d, const st_tensor* q, const st_tensor
       const int j = vis[x0 + x];
       a.t.k[x] = d->k_ptr[j]; a.t.v[x] = d->v_ptr[j]; a.t.k_offset[x] = d->k_offset[j];
       a.dk[x] = dk_acc[j]; a.dv[x] = dv_acc[j];
+      a.dk_lowp[x] = dk_lowp ? dk_lowp[j] : nullptr;
+      a.dv_lowp[x] = dk_lowp ? dv_lowp[j] : nullptr;
     }
+    a.kv_assign = assign ? ~0ull : 0ull;
+    if (d->dtype != ST_BF16 && assign)              // the fp32 kernels only add
+      for (int x = 0; x < cnt; ++x) {
+        ST_HIP(st::launch_zero(a.dk[x], n_kv * (int64_t)sizeof(float), stream), "dk_acc fill");
+        ST_HIP(st::launch_zero(a.dv[x], n_kv * (int64_t)sizeof(float), stream), "dv_acc fill");
+      }
     ST_HIP(launch_bwd(d->dtype, a, stream), "backward launch");
   }
   return ST_OK;

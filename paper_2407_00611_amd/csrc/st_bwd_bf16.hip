@@ -483,19 +483,42 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
         std::swap(a.t.k_offset[j], a.t.k_offset[j - 1]);
         std::swap(a.dk[j], a.dk[j - 1]);
         std::swap(a.dv[j], a.dv[j - 1]);
+        std::swap(a.dk_lowp[j], a.dk_lowp[j - 1]);
+        std::swap(a.dv_lowp[j], a.dv_lowp[j - 1]);
+        const uint64_t bj = (a.kv_assign >> j) & 1, bi = (a.kv_assign >> (j - 1)) & 1;
+        a.kv_assign = (a.kv_assign & ~((1ull << j) | (1ull << (j - 1)))) | (bi << j) | (bj << (j - 1));
       }
+  }
+  // Assignment and bf16 copies can be left to the fast dK/dV kernel for the chunks it alone writes: full tiles
+  // only, every query row sees every key.  Every other chunk is zeroed here first (then added to as usual) and
+  // cast by a launch of its own at the end.
+  const int64_t n_kv = (int64_t)a.s.B * a.s.Sk * a.s.Hkv * a.s.D;
+  void* cast_dk[kMaxTable];
+  void* cast_dv[kMaxTable];
+  for (int c = 0; c < a.t.n; ++c) {
+    cast_dk[c] = cast_dv[c] = nullptr;
+    const bool fast_only = a.dkv_fast && dkv_chunk_fast_only(a.s, a.t.k_offset[c]);
+    if (fast_only && ((a.dk_lowp[c] == nullptr) == (a.dv_lowp[c] == nullptr))) continue;
+    if ((a.kv_assign >> c) & 1) {
+      hipError_t ez = launch_zero(a.dk[c], n_kv * (int64_t)sizeof(float), stream);
+      if (ez == hipSuccess) ez = launch_zero(a.dv[c], n_kv * (int64_t)sizeof(float), stream);
+      if (ez != hipSuccess) return ez;
+      a.kv_assign &= ~(1ull << c);
+    }
+    cast_dk[c] = a.dk_lowp[c];
+    cast_dv[c] = a.dv_lowp[c];
+    a.dk_lowp[c] = a.dv_lowp[c] = nullptr;
   }
   hipError_t e = hipSuccess;
   {
     // With the fast kernel on, the general one only has the masked and ragged blocks left: chunks whose every
-    // block is the fast kernel's (full tiles, every row sees every key) are left out of its grid, which would
-    // otherwise consist mostly of workgroups that find nothing to do.
+    // block is the fast kernel's (dkv_chunk_fast_only) are left out of its grid, which would otherwise consist
+    // mostly of workgroups that find nothing to do.
     BwdArgs g = a;
-    if (a.dkv_fast && a.s.Sk % kDkvFastKeys == 0 && a.s.Sq % kDkvFastRows == 0) {
+    if (a.dkv_fast) {
       g.t.n = 0;
       for (int c = 0; c < a.t.n; ++c) {
-        const bool all_fast = !a.s.causal || q_pos(a.s, 0) >= a.t.k_offset[c] + a.s.Sk - 1;
-        if (all_fast) continue;
+        if (dkv_chunk_fast_only(a.s, a.t.k_offset[c])) continue;
         g.t.k[g.t.n] = a.t.k[c];
         g.t.v[g.t.n] = a.t.v[c];
         g.t.k_offset[g.t.n] = a.t.k_offset[c];
@@ -515,6 +538,11 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (a.dkv_fast) {
     e = launch_bwd_dkv_fast(a, stream);
+    if (e != hipSuccess) return e;
+  }
+  for (int c = 0; c < a.t.n; ++c) {
+    if (cast_dk[c]) e = launch_cast(a.dk[c], cast_dk[c], n_kv, ST_BF16, stream);
+    if (e == hipSuccess && cast_dv[c]) e = launch_cast(a.dv[c], cast_dv[c], n_kv, ST_BF16, stream);
     if (e != hipSuccess) return e;
   }
   static const int dq_fast_env = [] {

@@ -213,6 +213,16 @@ __global__ __launch_bounds__(256) void fill_state_kernel(float* __restrict__ o, 
   if (v < n_lse) lse[v] = -INFINITY;
 }
 
+// n dwords to zero, four per lane (the tail lane by lane)
+__global__ __launch_bounds__(256) void zero_kernel(uint32_t* __restrict__ dst, int64_t n) {
+  const int64_t v = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (v + 4 <= n && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+    *reinterpret_cast<uint4*>(dst + v) = make_uint4(0u, 0u, 0u, 0u);
+  } else {
+    for (int64_t i = v; i < n && i < v + 4; ++i) dst[i] = 0u;
+  }
+}
+
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
 
 }  // namespace
@@ -286,6 +296,14 @@ hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hi
   ProfScope prof("cast", s);
   hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n_vec + tail)), dim3(256), 0, s, (const float4*)src,
                      (uint2*)dst, n_vec, src + n_vec * 4, (uint16_t*)dst + n_vec * 4, tail);
+  return hipGetLastError();
+}
+
+hipError_t launch_zero(void* dst, int64_t bytes, hipStream_t s) {
+  if (bytes <= 0) return hipSuccess;
+  const int64_t n = bytes / 4;
+  ProfScope prof("zero", s);
+  hipLaunchKernelGGL(zero_kernel, dim3(blocks_for((n + 3) / 4)), dim3(256), 0, s, (uint32_t*)dst, n);
   return hipGetLastError();
 }
 

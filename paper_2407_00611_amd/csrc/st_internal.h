@@ -84,6 +84,12 @@ struct BwdArgs {
   float* dv[kMaxTable];
   int32_t dkv_fast;    // 1: the fast dK/dV kernel runs too and owns the blocks dkv_fast_first_block describes
   int32_t dq_fast;     // 1: the fast dQ kernel runs too and owns the tiles dq_fast_tiles describes
+  // dK / dV work of a chunk's last visit folded into the launch (bf16 path).  On entry to launch_bwd_bf16 they
+  // state what the caller wants for every table entry; the launcher keeps them for the entries whose every
+  // block belongs to the fast kernel (their only writer) and serves the others with fill / cast launches.
+  uint64_t kv_assign;          // bit c: dk[c] / dv[c] are overwritten, not added to
+  void* dk_lowp[kMaxTable];    // nullable per entry: the final dk[c] / dv[c] rounded to bf16, dense [B,Sk,Hkv,D]
+  void* dv_lowp[kMaxTable];
   int32_t* queue;      // nullable, kQueueInts ints of device memory: the fast dK/dV kernel hands its key tiles out
                        // through it (one counter per XCD), so that XCDs that run faster take more of them
 };
@@ -110,6 +116,17 @@ __host__ __device__ inline int dkv_fast_first_block(const Shape& s, int64_t k0, 
   if (!s.causal) return 0;
   const int d = q_row_of(s, k0 + tile_key0 + kDkvFastKeys - 1);     // first row index that sees the last key
   return (d + kDkvFastRows - 1) / kDkvFastRows;
+}
+
+// True when the fast dK/dV kernel alone works on a chunk of full tiles: every query row sees either all of the
+// chunk's keys or none of them, and the rows that see it start at a block boundary, so no block needs a mask.
+// (With one run of rows these are the chunks that end before the shard begins; with two runs also the chunks
+// that lie between the two.)
+__host__ __device__ inline bool dkv_chunk_fast_only(const Shape& s, int64_t k0) {
+  if (s.Sk % kDkvFastKeys != 0 || s.Sq % kDkvFastRows != 0) return false;
+  if (!s.causal) return true;
+  const int r_any = q_row_of(s, k0), r_all = q_row_of(s, k0 + s.Sk - 1);
+  return r_any == r_all && r_all % kDkvFastRows == 0 && r_all < s.Sq;
 }
 
 // Optional per-kernel timing (st_profile_begin / st_profile_end): while enabled, a ProfScope
@@ -160,5 +177,6 @@ hipError_t launch_delta(const View& d_o, int d_o_dtype, const View& o, int o_dty
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, hipStream_t s);
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hipStream_t s);
 hipError_t launch_fill_state(float* o, float* lse, int64_t n_o, int64_t n_lse, hipStream_t s);
+hipError_t launch_zero(void* dst, int64_t bytes, hipStream_t s);   // bytes % 4 == 0, dst 4-byte aligned
 
 }  // namespace st

@@ -153,6 +153,79 @@ def test_dkv_tiles_through_the_queue(D):
         assert torch.equal(a[1][j], c[1][j]) and torch.equal(a[2][j], c[2][j])
 
 
+LAST_CASES = [
+    # three chunks the fast dK/dV kernel alone writes (it assigns and casts them itself) and the diagonal one,
+    # which is zeroed, added to and cast by launches of their own
+    si.Workload("last_mixed_d128", 101, "bf16", 1, 4, 2, 128, 96, 512, 4, 4 * 512 - 96, True, True),
+    si.Workload("last_mixed_d64", 102, "bf16", 2, 4, 4, 64, 64, 256, 3, 3 * 256 - 64, True, True),
+    # no chunk qualifies (ragged sizes): everything through the fill / add / cast launches
+    si.Workload("last_ragged_d128", 103, "bf16", 1, 2, 1, 128, 100, 300, 3, 2 * 300, True, True),
+    # full mask, 520 key tiles: the fast kernel's queue path with the assigning, casting epilogue
+    si.Workload("last_queue_d128", 104, "bf16", 1, 8, 8, 128, 64, 256, 65, 0, False, True),
+]
+
+
+@pytest.mark.parametrize("w", LAST_CASES, ids=[w.name for w in LAST_CASES])
+def test_ring_bwd_last_visit(w):
+    """st_ring_bwd_last against st_ring_bwd: assigning into accumulators full of NaN gives, bit for bit, what adding
+    into zeroed ones gives; the bf16 copies are the rounded accumulators; adding (no assign) with copies gives
+    start + contribution; a listed chunk in the causal future is set to zero."""
+    inp = si.make_inputs(w)
+    q, ks, vs, d_o = upload(inp)
+    n = w.n_chunks
+    koffs = [w.k_offset(j) for j in range(n)]
+    order = list(range(n))
+    o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, st.ST_RING_FUSED)
+    zeros = lambda: [torch.zeros(k.shape, device="cuda") for k in ks]
+    nans = lambda: [torch.full(k.shape, float("nan"), device="cuda") for k in ks]
+    lows = lambda: [torch.full(k.shape, float("nan"), device="cuda", dtype=torch.bfloat16) for k in ks]
+    dq0, dk0, dv0 = torch.zeros_like(o), zeros(), zeros()
+    st.st_ring_bwd(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq0, dk0, dv0)
+    q_pos, k_pos = positions(w)
+    _, dk_r, dv_r = oa.attention_backward(inp.q, inp.k, inp.v, inp.d_o, q_pos, k_pos, w.causal, w.scale)
+    for j in range(n):
+        assert_close(host(dk0[j]), dk_r[j], "bf16", f"dk[{j}]")
+        assert_close(host(dv0[j]), dv_r[j], "bf16", f"dv[{j}]")
+    for mode in (st.ST_RING_FUSED, st.ST_RING_STEPWISE):
+        print(f"[{w.name}] assign + copies, mode {mode}", flush=True)
+        dq1, dk1, dv1, lk1, lv1 = torch.zeros_like(o), nans(), nans(), lows(), lows()
+        st.st_ring_bwd_last(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq1, dk1, dv1,
+                            assign=True, dk_lowp=lk1, dv_lowp=lv1, mode=mode)
+        if mode == st.ST_RING_FUSED:                 # step by step dq is added up in another order
+            assert torch.equal(dq0, dq1)
+        for j in range(n):
+            assert torch.equal(dk0[j], dk1[j]) and torch.equal(dv0[j], dv1[j]), f"chunk {j}"
+            assert torch.equal(lk1[j], dk1[j].to(torch.bfloat16)) and torch.equal(lv1[j], dv1[j].to(torch.bfloat16)), f"copy {j}"
+    print(f"[{w.name}] assign, no copies", flush=True)
+    dq2, dk2, dv2 = torch.zeros_like(o), nans(), nans()
+    st.st_ring_bwd_last(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq2, dk2, dv2, assign=True)
+    for j in range(n):
+        assert torch.equal(dk0[j], dk2[j]) and torch.equal(dv0[j], dv2[j]), f"chunk {j}"
+    print(f"[{w.name}] add, copies of some chunks", flush=True)
+    start = [torch.randn(k.shape, device="cuda") for k in ks]
+    dq3, dk3, dv3 = torch.zeros_like(o), [t.clone() for t in start], [t.clone() for t in start]
+    lk3, lv3 = lows(), lows()
+    some = [(lk3[j] if j % 2 == 0 else None) for j in range(n)], [(lv3[j] if j % 2 == 0 else None) for j in range(n)]
+    st.st_ring_bwd_last(q, ks, vs, d_o, o_low, lse, w.q_offset, koffs, w.causal, w.scale, order, dq3, dk3, dv3,
+                        assign=False, dk_lowp=some[0], dv_lowp=some[1])
+    for j in range(n):
+        assert_close(host(dk3[j]) - host(start[j]), dk_r[j], "bf16", f"dk[{j}] - start")
+        assert_close(host(dv3[j]) - host(start[j]), dv_r[j], "bf16", f"dv[{j}] - start")
+        if j % 2 == 0:
+            assert torch.equal(lk3[j], dk3[j].to(torch.bfloat16)) and torch.equal(lv3[j], dv3[j].to(torch.bfloat16))
+        else:
+            assert torch.isnan(lk3[j].float()).all()          # not asked for: untouched
+    if w.causal:
+        print(f"[{w.name}] a listed chunk in the causal future", flush=True)
+        koffs_f = koffs[:-1] + [w.q_offset + w.Sq + 5]          # the last chunk now starts after the last query
+        dq4, dk4, dv4, lk4, lv4 = torch.zeros_like(o), nans(), nans(), lows(), lows()
+        o4, lse4, o_low4 = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs_f, w.causal, w.scale, order, None, st.ST_RING_FUSED)
+        st.st_ring_bwd_last(q, ks, vs, d_o, o_low4, lse4, w.q_offset, koffs_f, w.causal, w.scale, order, dq4, dk4, dv4,
+                            assign=True, dk_lowp=lk4, dv_lowp=lv4)
+        assert not dk4[-1].any() and not dv4[-1].any() and not lk4[-1].any() and not lv4[-1].any()
+        assert not torch.isnan(dk4[0]).any() and not torch.isnan(lk4[0].float()).any()
+
+
 BHSD_CASES = [
     # a chunk table of the maximum length (64 entries) of 64-key chunks: forward and dQ loops
     si.Workload("fast_bhsd_64chunks", 97, "bf16", 2, 4, 2, 128, 288, 64, 64, 64 * 64 - 288, True, True),
