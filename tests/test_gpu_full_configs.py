@@ -64,11 +64,17 @@ def test_full_size_sampled_rows(cfg):
         keep[:, torch.from_numpy(rows[h]).cuda(), h] = True
     d_o_b = torch.where(keep, d_o, torch.zeros_like(d_o))
     dq_b = torch.zeros_like(o)
-    dk = [torch.zeros(k.shape, device="cuda") for k in ks]
-    dv = [torch.zeros(k.shape, device="cuda") for k in ks]
-    st.st_ring_bwd(q, ks, vs, d_o_b, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq_b, dk, dv,
-                   st.ST_RING_FUSED)
+    # as bench.py launches the backward: dK / dV assigned (the accumulators start as NaN) and rounded by their kernels
+    dk = [torch.full(k.shape, float("nan"), device="cuda") for k in ks]
+    dv = [torch.full(k.shape, float("nan"), device="cuda") for k in ks]
+    dk_low = [torch.full(k.shape, float("nan"), device="cuda", dtype=torch.bfloat16) for k in ks]
+    dv_low = [torch.full(k.shape, float("nan"), device="cuda", dtype=torch.bfloat16) for k in ks]
+    st.st_ring_bwd_last(q, ks, vs, d_o_b, o_low, lse, w.q_where, koffs, w.causal, w.scale, order, dq_b, dk, dv,
+                        assign=True, dk_lowp=dk_low, dv_lowp=dv_low, mode=st.ST_RING_FUSED)
     torch.cuda.synchronize()
+    for j in range(w.n_chunks):
+        assert torch.equal(dk_low[j], dk[j].to(torch.bfloat16)) and torch.equal(dv_low[j], dv[j].to(torch.bfloat16)), j
+    del dk_low, dv_low
     assert float(torch.where(keep, torch.zeros_like(dq_b), dq_b).abs().max()) == 0.0, "dQ outside the sampled rows"
     for h in range(w.Hq):
         idx = torch.from_numpy(rows[h]).cuda()

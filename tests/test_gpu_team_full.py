@@ -80,9 +80,18 @@ def test_team_gathered_full_size_sampled_rows():
         keep[:, idx[h], h] = True
     d_o_b = torch.where(keep, d_o, torch.zeros_like(d_o))
     dq_b, dk, dv = grads()
-    st.st_ring_bwd(q, ks, vs, d_o_b, o_team_low, lse_team, w.q_offset, koffs, w.causal, w.scale, mine, dq_b, dk, dv,
-                   st.ST_RING_FUSED)
+    # as bench.py launches it: dK / dV assigned (the accumulators start as NaN) and rounded by their kernels
+    for t in dk + dv:
+        if t is not None:
+            t.fill_(float("nan"))
+    dk_low = [torch.full(t.shape, float("nan"), device="cuda", dtype=torch.bfloat16) if t is not None else None for t in dk]
+    dv_low = [torch.full(t.shape, float("nan"), device="cuda", dtype=torch.bfloat16) if t is not None else None for t in dv]
+    st.st_ring_bwd_last(q, ks, vs, d_o_b, o_team_low, lse_team, w.q_offset, koffs, w.causal, w.scale, mine, dq_b, dk, dv,
+                        assign=True, dk_lowp=dk_low, dv_lowp=dv_low, mode=st.ST_RING_FUSED)
     torch.cuda.synchronize()
+    for j in mine:
+        assert torch.equal(dk_low[j], dk[j].to(torch.bfloat16)) and torch.equal(dv_low[j], dv[j].to(torch.bfloat16)), j
+    del dk_low, dv_low
     assert float(torch.where(keep, torch.zeros_like(dq_b), dq_b).abs().max()) == 0.0, "dQ outside the sampled rows"
     for h in range(w.Hq):
         assert torch.equal(dq_b[:, idx[h], h], dq[:, idx[h], h]), "a row's dQ must not depend on other rows' dO"
