@@ -134,3 +134,38 @@ def test_forward_workspace_covers_every_visited_subset():
     assert sizes == sorted(sizes)                             # grows with the table ...
     assert need(150) == need(64) == need(256)                 # ... up to one launch's table, and stays there
     assert need(64, Sq=4096, Hq=32) == need(1, Sq=4096, Hq=32)  # enough query tiles to fill the chip: never split
+
+
+def test_ring_bwd_last_validation_fails_before_any_launch():
+    """Fake device pointers: the arguments st_ring_bwd_last adds are checked on the host."""
+    lib = api._lib
+    n = 2
+    k_ptr = (C.c_void_p * n)(0x10000, 0x20000)
+    v_ptr = (C.c_void_p * n)(0x30000, 0x40000)
+    k_off = (C.c_int64 * n)(0, 8)
+    vpp = C.POINTER(C.c_void_p)
+
+    def desc(dtype):
+        return api.st_ring_desc(dtype, 1, 2, 1, 64, 8, 8, 16, 1, 0.125, n, C.cast(k_ptr, vpp), C.cast(v_ptr, vpp),
+                                512, 64, 64, 512, 64, 64, C.cast(k_off, C.POINTER(C.c_int64)), 0, 0)
+
+    def call(dtype=1, flags=0, lk=None, lv=None, ws=0x900000, ws_bytes=1 << 20):
+        d = desc(dtype)
+        t = api.st_tensor(0x1000, 1024, 128, 64)
+        order = (C.c_int32 * n)(0, 1)
+        dk = (C.c_void_p * n)(0x50000, 0x60000)
+        dv = (C.c_void_p * n)(0x70000, 0x80000)
+        return lib.st_ring_bwd_last(C.byref(d), C.byref(t), C.byref(t), C.byref(t), dtype, C.c_void_p(0x2000), order, n, 1,
+                                    C.c_void_p(0x3000), C.cast(dk, vpp), C.cast(dv, vpp), flags,
+                                    C.cast(lk, vpp) if lk is not None else None, C.cast(lv, vpp) if lv is not None else None,
+                                    C.c_void_p(ws), ws_bytes, None)
+
+    both = (C.c_void_p * n)(0xa0000, 0xb0000)
+    half = (C.c_void_p * n)(0xa0000, None)
+    odd = (C.c_void_p * n)(0xa0004, 0xb0000)
+    assert call(flags=2) == 1 and "kv_flags" in st.st_last_error()
+    assert call(lk=both) == 1                                  # one table without the other
+    assert call(lk=both, lv=half) == 1                         # one entry without the other
+    assert call(lk=odd, lv=both) == 3                          # misaligned copy
+    assert call(dtype=0, lk=both, lv=both) == 2                # bf16 copies of an fp32 problem
+    assert call(flags=1, lk=both, lv=both, ws=0) == 5          # arguments fine: stops at the missing workspace
