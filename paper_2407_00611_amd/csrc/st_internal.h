@@ -94,6 +94,8 @@ struct BwdArgs {
                        // through it (one counter per XCD), so that XCDs that run faster take more of them
 };
 constexpr int kQueueInts = 8 * 32;   // 8 counters, 128 bytes apart
+// passed by value: the kernel-argument segment holds 4096 bytes, 256 of them the implicit arguments
+static_assert(sizeof(BwdArgs) <= 4096 - 256 && sizeof(FwdArgs) <= 4096 - 256, "argument structs must fit the kernel-argument segment");
 
 // n partial states of the same query rows (each O fp32 [B,Sq_in,Hq,D], lse fp32 [B,Hq,Sq_in]) and the run of
 // rows [row0, row0 + Sq_out) the combined state keeps.
