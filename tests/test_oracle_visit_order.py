@@ -31,6 +31,20 @@ def test_hand_evaluated_maps():
     assert all(ov.get_p2p_config(g // 2, g % 2, 4, 2)[0] == ov.get_p2p_config(g // 2, g % 2, 4, 2)[1]
                for g in range(8))
     assert ov.sub_rings(8, 2) == [[0, 2], [1, 3], [4, 6], [5, 7]]
+    # four GPUs per sub-ring: next and last differ, both outputs of the algorithm are pinned
+    assert [ov.get_p2p_config(g // 2, g % 2, 8, 2)[0] for g in range(16)] == GOLD["P16_C2_next"]
+    assert [ov.get_p2p_config(g // 2, g % 2, 8, 2)[1] for g in range(16)] == GOLD["P16_C2_last"]
+    assert [ov.get_p2p_config(g, 0, 16, 1)[1] for g in range(16)] == GOLD["P16_C1_last"]
+
+
+@pytest.mark.parametrize("P,C", [(4, 1), (8, 2), (16, 2), (32, 2), (64, 4), (36, 3), (27, 3)])
+def test_last_is_the_inverse_of_next(P, C):
+    """A GPU receives from the GPU that sends to it: last(next(g)) = g = next(last(g)) for every rank."""
+    d_a, d_t = C, P // C
+    nxt = [ov.get_p2p_config(g // C, g % C, d_t, d_a)[0] for g in range(P)]
+    lst = [ov.get_p2p_config(g // C, g % C, d_t, d_a)[1] for g in range(P)]
+    assert sorted(nxt) == list(range(P)) and sorted(lst) == list(range(P))
+    assert all(lst[nxt[g]] == g and nxt[lst[g]] == g for g in range(P))
 
 
 @pytest.mark.parametrize("P,C", [(1, 1), (4, 1), (4, 2), (8, 2), (16, 1), (16, 2), (16, 4), (32, 4),
