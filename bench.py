@@ -37,15 +37,39 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
 def hbm_traffic(kernel: str, workload: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload.split('_')[0]}_hbm_traffic.txt")
+    """(HBM bytes per launch of `kernel`, file they come from): counters cannot be read from inside this run, so
+    the figure is the one in the committed rocprofv3 counter summary of the same kernel and workload, if any."""
+    name = f"{kernel}_{workload.split('_')[0]}_hbm_traffic.txt"
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, "profiles", name)):
             if line.startswith("traffic_bytes_per_launch"):
-                return int(line.split("=")[1])
+                return int(line.split("=")[1]), f"profiles/{name}"
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def mfma_ceiling(st, torch, data) -> dict:
+    """What the matrix units sustain with nothing else running (st_mfma_probe: a loop of v_mfma_f32_32x32x16_bf16
+    only, one workgroup per compute unit), on all-ones operands and on the workload's own Q values: the rate
+    depends on the data because the chip runs at its power limit.  Median of 5 launches of about 10 ms each."""
+    facts = st.st_device_facts()
+    sink = torch.empty(facts["compute_units"] * 256, dtype=torch.float32, device="cuda")
+    ones = torch.ones(1 << 20, dtype=torch.bfloat16, device="cuda")
+    out = {}
+    for name, ops in (("ones", ones), ("workload_q", data.reshape(-1))):
+        iters = 20000
+        st.st_mfma_probe(ops, 200, sink)
+        ms = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flop = st.st_mfma_probe(ops, iters, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        out[name] = round(flop / (sorted(ms)[2] * 1e-3) / 1e12, 1)
+    return out
 
 
 def merge_pass(st, torch, w) -> dict:
@@ -104,8 +128,8 @@ def combine_pass(st, torch, states_o, states_l, n_own, w) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 1..5 (default 4)")
     ap.add_argument("--mode", choices=["fused", "stepwise"], default="fused")
     ap.add_argument("--shape", choices=["ring", "team", "dit", "zigzag"], default="ring",
@@ -238,11 +262,18 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # exactly --steps steps between two synchronisations (host clock: ms_per_step), each one also bracketed by HIP
+    # events on the launch stream (median and minimum); the accumulators are re-zeroed inside the step (counted)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    ev[0].record()
+    for i in range(args.steps):
         step()
+        ev[i + 1].record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
+    ms_median, ms_min = ms_each[len(ms_each) // 2], ms_each[0]
 
     # ---- per-kernel durations with HIP events on the launch stream (separate, untimed steps) ---------
     prof_steps = max(1, min(args.steps, 5))
@@ -269,20 +300,29 @@ def main() -> int:
         if name in algo and mode == st.ST_RING_FUSED:
             per_kernel[name]["algorithmic_tflops"] = round(algo[name] / (avg * 1e-3) / 1e12, 1)
     dom = max((n for n in kernels if n in algo), key=lambda n: kernels[n][1], default=None)
+    facts = st.st_device_facts()
+    # nominal peak from the device the run is on: CUs x 4096 bf16 flop per clock and CU x maximum shader clock
+    peak_nominal = facts["compute_units"] * 4096 * facts["max_clock_mhz"] * 1e6 / 1e12 if bf16 else None
+    ceiling = mfma_ceiling(st, torch, q) if bf16 else None
     roofline = None
     if dom is not None:
         launches, total_ms = kernels[dom]
         step_ms = total_ms / prof_steps                        # all launches of that kernel in one step
         achieved = algo[dom] / (step_ms * 1e-3) / 1e12
         peak = PEAK_BF16_TFLOPS if bf16 else 157.3
+        traffic, traffic_source = hbm_traffic(dom, w.name)
         roofline = {"kernel": dom, "bound": "mfma" if bf16 else "alu", "achieved": round(achieved, 1), "peak": peak,
-                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": hbm_traffic(dom, w.name),
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
+                    "traffic_source": traffic_source,
                     "avg_launch_ms": round(total_ms / max(launches, 1), 4)}
+        if ceiling:
+            roofline["frac_of_measured_mfma_peak"] = round(achieved / ceiling["workload_q"], 4)
 
     out = {
         "metric": "fwd+bwd attention TFLOP/s on 1 MI355X + % of bf16 MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "ms_median": round(ms_median, 4), "ms_min": round(ms_min, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "Sq": w.Sq, "Sk": w.Sk,
                    "n_chunks": w.n_chunks, "causal": w.causal, "q_offset": w.q_offset, "q_seg": w.q_seg, "q_offset2": w.q_offset2, "mode": args.mode,
@@ -290,6 +330,14 @@ def main() -> int:
                    "visit_order": f"P={w.ring_P},C={w.ring_C},rank={w.ring_rank}" if w.ring_P else "natural",
                    "passes": "fwd+bwd" if w.backward else "fwd"},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "device": {"name": facts["name"], "arch": facts["arch"], "cus": facts["compute_units"], "xcds": facts["xcds"],
+                   "max_clock_mhz": facts["max_clock_mhz"], "memory_clock_mhz": facts["memory_clock_mhz"],
+                   "memory_bus_bits": facts["memory_bus_bits"], "hbm_gib": round(facts["hbm_bytes"] / 2**30, 1),
+                   "host_threads": os.cpu_count()},
+        "peak_bf16_tflops": {"divided_by": PEAK_BF16_TFLOPS,
+                             "from_device_properties": round(peak_nominal, 1) if peak_nominal else None},
+        "measured_mfma_peak_tflops": ceiling,
+        "pct_of_measured_mfma_peak": round(100.0 * value / ceiling["workload_q"], 2) if ceiling else None,
         "algorithmic_tflop": {"fwd": round(fwd_flop / 1e12, 4), "bwd": round(bwd_flop / 1e12, 4)},
         "roofline": roofline,
         "kernels": per_kernel,

@@ -32,6 +32,14 @@
  *   - Supported: ST_F32 with D <= 256 (plain kernels), ST_BF16 with D == 128
  *     or D == 64 (MFMA kernels, fp32 accumulation).  Anything else returns
  *     ST_ERR_UNSUPPORTED.
+ *   - Precision of the ST_BF16 path: P and dS are rounded to bf16 before the
+ *     second contractions, and every kernel, forward and backward, evaluates
+ *     the scores from the same operand Q' = bf16(Q * scale * log2 e), so that
+ *     the matrix units deliver exponents directly.  That is attention of a
+ *     query perturbed by at most 2^-9 relative per element: the scores move by
+ *     about 1e-3 of their spread (standard deviation over a row), lse likewise,
+ *     and backward and forward stay consistent with each other (recomputed
+ *     probabilities sum to one over a row).
  */
 #ifndef STARTRAIL_H
 #define STARTRAIL_H
@@ -157,7 +165,12 @@ st_status st_attn_delta(const st_block_desc* desc, const st_tensor* d_o, const s
 st_status st_attn_block_bwd(const st_block_desc* desc, const st_tensor* q, const st_tensor* k,
                             const st_tensor* v, const st_tensor* d_o, const float* lse_final,
                             const float* delta, float* dq_acc, float* dk_acc, float* dv_acc,
-                            void* hip_stream);
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+/* workspace (nullable): device, 256-byte aligned, at least st_attn_block_bwd_workspace_bytes(desc) bytes (0 for
+ * ST_F32).  With it the ST_BF16 path keeps a scaled copy of Q there and its hand-scheduled dK/dV kernel takes
+ * part; without it the same values are computed by the general kernel, at a lower rate.  Contents mean nothing
+ * between calls; calls that share a workspace must be ordered on one stream. */
+size_t st_attn_block_bwd_workspace_bytes(const st_block_desc* desc);
 
 /* ---- fp32 -> storage dtype (round to nearest even), n contiguous elements ---- */
 st_status st_cast_from_f32(const float* src, void* dst, int64_t n, int32_t dst_dtype, void* hip_stream);
@@ -219,8 +232,8 @@ st_status st_schedule_report(int32_t P, int32_t C, int64_t B, int64_t N, int64_t
  * Forward outputs: o_acc fp32 [B,Sq,Hq,D], lse fp32 [B,Hq,Sq] (overwritten); o_lowp nullable,
  *   [B,Sq,Hq,D] in desc->dtype.
  * workspace: device, >= st_ring_workspace_bytes(desc, mode, backward) bytes, 256-byte aligned.  Its contents
- *   are the library's (partial states, Delta, the tile counters of the dK/dV launch) and mean nothing between
- *   calls; calls that share a workspace must be ordered on one stream. */
+ *   are the library's (partial states, Delta, the tile counters of the dK/dV launch, the scaled copy of Q) and
+ *   mean nothing between calls; calls that share a workspace must be ordered on one stream. */
 size_t st_ring_workspace_bytes(const st_ring_desc* desc, int32_t mode, int32_t backward);
 
 st_status st_ring_fwd(const st_ring_desc* desc, const st_tensor* q, const int32_t* order,
@@ -268,6 +281,33 @@ typedef struct {
 } st_profile_entry;
 st_status st_profile_begin(void);
 st_status st_profile_end(st_profile_entry* out, int32_t max_entries, int32_t* n_entries);
+
+/* ---- the device as the library sees it, for benchmark reports (not part of the method) ----
+ * Facts of the current HIP device: compute units, XCDs (accelerator dies with an L2 each; 8 when the runtime
+ * does not tell), the maximum shader and memory clocks, bus width and memory size.  `out` is host memory. */
+typedef struct {
+  char    name[64];
+  char    arch[32];
+  int32_t compute_units;
+  int32_t xcds;
+  int32_t max_clock_mhz;
+  int32_t memory_clock_mhz;
+  int32_t memory_bus_bits;
+  int64_t hbm_bytes;
+} st_device_report;
+st_status st_device_facts(st_device_report* out);
+
+/* ---- MFMA-only loop for benchmarks (not part of the method) ----
+ * One workgroup of four wavefronts per compute unit; every wavefront loads 16 operand fragments (16 bytes per
+ * lane each) from `operands` and then issues iters x 32 v_mfma_f32_32x32x16_bf16 on them and nothing else.
+ * Timed by the caller (events on the stream), it gives the rate the matrix units sustain on THAT data, which is
+ * the ceiling to compare an attention kernel with: the chip runs at its power limit, and the limit depends on
+ * the operand values.
+ *   operands  device, 16-byte aligned, operand_bytes >= 65536 bytes of bf16 values (read with wrap-around)
+ *   sink      device, sink_floats >= 256 * compute units floats (overwritten; keeps the loop alive)
+ *   flop      host, nullable: floating point operations the launch executes (2 per multiply-add) */
+st_status st_mfma_probe(const void* operands, int64_t operand_bytes, int32_t iters, float* sink,
+                        int64_t sink_floats, double* flop, void* hip_stream);
 
 /* ---- misc ---- */
 const char* st_status_str(st_status s);

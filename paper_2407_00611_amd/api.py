@@ -54,6 +54,12 @@ class st_comm_report(C.Structure):
                 ("startrail_p2p_seconds", C.c_double), ("startrail_collective_seconds", C.c_double)]
 
 
+class st_device_report(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("arch", C.c_char * 32), ("compute_units", C.c_int32), ("xcds", C.c_int32),
+                ("max_clock_mhz", C.c_int32), ("memory_clock_mhz", C.c_int32), ("memory_bus_bits", C.c_int32),
+                ("hbm_bytes", C.c_int64)]
+
+
 class st_profile_entry(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("launches", C.c_int32), ("total_ms", C.c_float)]
 
@@ -75,7 +81,8 @@ def _load() -> C.CDLL:
         "st_attn_combine": (C.c_int, [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32, f32p, f32p, C.c_int32, vp, vp]),
         "st_attn_delta": (C.c_int, [D, T, T, C.c_int32, f32p, vp]),
-        "st_attn_block_bwd": (C.c_int, [D, T, T, T, T, f32p, f32p, f32p, f32p, f32p, vp]),
+        "st_attn_block_bwd": (C.c_int, [D, T, T, T, T, f32p, f32p, f32p, f32p, f32p, vp, C.c_size_t, vp]),
+        "st_attn_block_bwd_workspace_bytes": (C.c_size_t, [D]),
         "st_cast_from_f32": (C.c_int, [f32p, vp, C.c_int64, C.c_int32, vp]),
         "st_visit_order": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, i32p, i32p]),
         "st_team_visit_order": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, i32p]),
@@ -88,6 +95,8 @@ def _load() -> C.CDLL:
         "st_ring_bwd_last": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
+        "st_device_facts": (C.c_int, [C.POINTER(st_device_report)]),
+        "st_mfma_probe": (C.c_int, [vp, C.c_int64, C.c_int32, f32p, C.c_int64, C.POINTER(C.c_double), vp]),
         "st_profile_begin": (C.c_int, []),
         "st_profile_end": (C.c_int, [C.POINTER(st_profile_entry), C.c_int32, C.POINTER(C.c_int32)]),
         "st_status_str": (C.c_char_p, [C.c_int]),
@@ -101,8 +110,8 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_combine", "st_attn_delta", "st_attn_block_bwd", "st_cast_from_f32",
-           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_last", "st_profile_begin",
+EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_combine", "st_attn_delta", "st_attn_block_bwd", "st_attn_block_bwd_workspace_bytes", "st_cast_from_f32",
+           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_last", "st_device_facts", "st_mfma_probe", "st_profile_begin",
            "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
@@ -142,6 +151,12 @@ def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
     return C.c_void_p(t.data_ptr() if t is not None and t.numel() else None)
 
 
+def _aligned(buf: torch.Tensor, a: int) -> Tuple[int, int]:
+    """First a-byte aligned address inside a byte buffer and the bytes from there to its end."""
+    ptr = (buf.data_ptr() + a - 1) // a * a
+    return ptr, buf.numel() * buf.element_size() - (ptr - buf.data_ptr())
+
+
 def _f32_dense(t: torch.Tensor, shape, name: str) -> torch.Tensor:
     if t.dtype != torch.float32 or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
         raise ValueError(f"{name} must be a contiguous fp32 tensor of shape {tuple(shape)}")
@@ -174,6 +189,24 @@ def st_status_str(status: int) -> str:
 
 def st_last_error() -> str:
     return _lib.st_last_error().decode()
+
+
+def st_device_facts() -> dict:
+    r = st_device_report()
+    _check(_lib.st_device_facts(C.byref(r)), "st_device_facts")
+    return {"name": r.name.decode(), "arch": r.arch.decode(), "compute_units": int(r.compute_units), "xcds": int(r.xcds),
+            "max_clock_mhz": int(r.max_clock_mhz), "memory_clock_mhz": int(r.memory_clock_mhz),
+            "memory_bus_bits": int(r.memory_bus_bits), "hbm_bytes": int(r.hbm_bytes)}
+
+
+def st_mfma_probe(operands: torch.Tensor, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueues the MFMA-only loop on `operands` (any contiguous tensor, read as bf16 bits); returns the flop it executes."""
+    if not operands.is_contiguous() or sink.dtype != torch.float32 or not sink.is_contiguous():
+        raise ValueError("operands must be contiguous, sink contiguous fp32")
+    flop = C.c_double(0.0)
+    _check(_lib.st_mfma_probe(_ptr(operands), operands.numel() * operands.element_size(), int(iters), _ptr(sink),
+                              sink.numel(), C.byref(flop), _stream(stream)), "st_mfma_probe")
+    return float(flop.value)
 
 
 def st_profile_begin() -> None:
@@ -250,8 +283,15 @@ def st_attn_delta(d_o, o, delta=None, stream=None) -> torch.Tensor:
     return delta
 
 
+def st_attn_block_bwd_workspace_bytes(q, k, q_offset: int, k_offset: int, causal: bool, scale: float) -> int:
+    d = _block_desc(q, k, q_offset, k_offset, causal, scale)
+    return int(_lib.st_attn_block_bwd_workspace_bytes(C.byref(d)))
+
+
 def st_attn_block_bwd(q, k, v, d_o, lse_final, delta, q_offset: int, k_offset: int, causal: bool, scale: float,
-                      dq_acc, dk_acc, dv_acc, stream=None) -> None:
+                      dq_acc, dk_acc, dv_acc, stream=None, workspace=None) -> None:
+    """workspace: a uint8 tensor of st_attn_block_bwd_workspace_bytes(...) bytes, None to have one allocated, or
+    False to pass none (the C call then keeps the dK/dV work in its general kernel)."""
     B, Sq, Hq, D = q.shape
     Sk, Hkv = k.shape[1], k.shape[2]
     _f32_dense(lse_final, (B, Hq, Sq), "lse_final"); _f32_dense(delta, (B, Hq, Sq), "delta")
@@ -259,8 +299,13 @@ def st_attn_block_bwd(q, k, v, d_o, lse_final, delta, q_offset: int, k_offset: i
     _f32_dense(dk_acc, (B, Sk, Hkv, D), "dk_acc"); _f32_dense(dv_acc, (B, Sk, Hkv, D), "dv_acc")
     d = _block_desc(q, k, q_offset, k_offset, causal, scale)
     tq, tk, tv, td = _view(q), _view(k), _view(v), _view(d_o)
+    need = int(_lib.st_attn_block_bwd_workspace_bytes(C.byref(d)))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need + 256, dtype=torch.uint8, device=q.device)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None or workspace is False else _aligned(workspace, 256)
     _check(_lib.st_attn_block_bwd(C.byref(d), C.byref(tq), C.byref(tk), C.byref(tv), C.byref(td), _ptr(lse_final),
-                                  _ptr(delta), _ptr(dq_acc), _ptr(dk_acc), _ptr(dv_acc), _stream(stream)),
+                                  _ptr(delta), _ptr(dq_acc), _ptr(dk_acc), _ptr(dv_acc), C.c_void_p(ws_ptr), ws_bytes,
+                                  _stream(stream)),
            "st_attn_block_bwd")
 
 

@@ -16,7 +16,7 @@ CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libstartrail.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
-SOURCES = ["st_api.cpp", "st_f32.hip", "st_elementwise.hip", "st_fwd_bf16.hip", "st_bwd_bf16.hip", "st_bwd_dkv_fast.hip", "st_bwd_dq_fast.hip", "st_fwd_fast.hip"]
+SOURCES = ["st_api.cpp", "st_runtime.cpp", "st_f32.hip", "st_elementwise.hip", "st_fwd_bf16.hip", "st_bwd_bf16.hip", "st_bwd_dkv_fast.hip", "st_bwd_dq_fast.hip", "st_fwd_fast.hip", "st_probe.hip"]
 # assembly main loops written out by generator scripts before compiling: (script, output)
 GENERATED = [("gen_bwd_dkv_asm.py", "st_bwd_dkv_asm.inc"), ("gen_bwd_dq_asm.py", "st_bwd_dq_asm.inc"),
              ("gen_fwd_asm.py", "st_fwd_asm.inc"), ("gen_fwd_asm.py 64", "st_fwd64_asm.inc"),
@@ -53,7 +53,7 @@ def build(verbose: bool = True) -> str:
             f.write(r.stdout)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objs, "-o", OUT]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", *objs, "-L/opt/rocm/lib", "-lhsa-runtime64", "-o", OUT]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")

@@ -13,13 +13,16 @@ resident K fragments and the score tiles in VGPRs) and a fixed interleave of MFM
 Work of one workgroup (4 wavefronts): 256 keys of one KV head of one chunk (64 per wavefront), against a
 run of 32-query blocks that see every one of those keys (no masking in here; blocks that need a mask go
 to the general kernel).  Per block and wavefront, with the MFMA C layout "lane = key column":
-    phase 1   E   = Q K'^T - lse log2e          A: Q rows from LDS,        B: resident K fragments, pre-multiplied
-                                                by scale * log2(e) (and rounded to bf16 again), C init: -lse log2e
+    phase 1   E   = Q' K^T - lse log2e          A: Q' rows from LDS (Q' = bf16(Q scale log2 e), made once per backward
+                                                by a pass of its own and shared with the other bf16 kernels, so that
+                                                every kernel evaluates the same scores), B: resident K fragments,
+                                                C init: -lse log2e
     phase 2   dP' = dO V^T - Delta              A: dO rows from LDS,       B: V rows from LDS, C init: -Delta
               VALU: P = exp2(E), bf16 pack                            (runs under phase 2 / 3 MFMAs)
     phase 3   dV^T += dO^T P                    A: dO^T by LDS transpose reads, B: packed P
               VALU: dS = P dP', bf16 pack (in place)                   (runs under phase 3 / 4 MFMAs)
-    phase 4   dK^T += Q^T dS                    A: Q^T by LDS transpose reads,  B: packed dS
+    phase 4   dK^T += Q'^T dS                   A: Q'^T by LDS transpose reads, B: packed dS  (the epilogue's factor is
+                                                ln 2 = scale / (scale log2 e) where dK = scale dS^T Q asks for scale)
 Q / dO tiles arrive by direct global->LDS loads into a 4-stage ring, three blocks ahead; the per-row
 statistics (lse, Delta) are loaded three blocks ahead into registers, transformed once and written to LDS
 by every wavefront (identical values), so that no per-element VALU work is spent on them.
@@ -73,7 +76,7 @@ IN_V = 176                                           # v[176:191]
  I_LF16, I_STAT_L) = (176, 178, 180, 181, 182, 183, 184, 185, 186, 187, 188, 189, 190, 191)
 IN_SA, IN_SB = 32, 48                                # s[32:47], s[48:63]
 S_QPTR, S_DOPTR, S_LSEPTR, S_DLPTR = 32, 34, 36, 38
-S_QBS, S_QHS, S_DOBS, S_DOHS, S_STATHS, S_NBLK, S_NSTEPS, S_CEXP = 40, 41, 42, 43, 44, 45, 46, 47
+S_QBS, S_QHS, S_DOBS, S_DOHS, S_STATHS, S_NBLK, S_NSTEPS = 40, 41, 42, 43, 44, 45, 46
 S_VPTR, S_VRS16, S_LDS, S_DKPTR, S_DVPTR, S_WAVE, S_RS32, S_SCALE = 48, 50, 51, 52, 54, 56, 57, 58
 S_FLAGS, S_DKLP, S_DVLP = 59, 60, 62                # epilogue variant; bf16 copies of the dK / dV tile (if asked for)
 # scalar temporaries (clobbered)
@@ -521,11 +524,6 @@ def generate():
     for t in (T_DBLK, T_DSTEP):
         e.raw(f"s_mov_b32 {sr(t)}, 0")
     e.raw(f"s_mov_b32 {sr(T_REM)}, {sr(S_NSTEPS)}")
-    e.comment("c = scale * log2(e) (there is no scalar floating point unit)")
-    e.raw(f"v_mov_b32 {vr(TMP)}, 0x3fb8aa3b")
-    e.raw(f"v_mul_f32 {vr(TMP)}, {sr(S_SCALE)}, {vr(TMP)}")
-    e.raw("s_nop 0")
-    e.raw(f"v_readfirstlane_b32 {sr(S_CEXP)}, {vr(TMP)}")
     e.raw(f"s_lshl_b32 {sr(T_M0)}, {sr(S_WAVE)}, 10")
     e.raw(f"s_add_u32 {sr(T_M0)}, {sr(T_M0)}, {sr(S_LDS)}")
     e.raw(f"s_mov_b32 {sr(T_HIMASK)}, 0")
@@ -582,15 +580,6 @@ def generate():
         e.raw(f"v_accvgpr_write_b32 {ar(i)}, 0")
     e.comment("statistics of block 0 to LDS stage 0, then block 2 requested (its statistics reuse block 0's registers)")
     e.raw(f"s_waitcnt vmcnt({NREQ})")
-    e.comment("K <- bf16(K * scale * log2(e)): the phase-1 MFMAs then deliver exponents in log2 units")
-    for i in range(0, 4 * KS * NKB, 4):
-        for j in range(4):
-            e.raw(f"v_lshlrev_b32 {vr(S0 + 2 * j)}, 16, {vr(i + j)}")
-            e.raw(f"v_and_b32 {vr(S0 + 1 + 2 * j)}, 0xffff0000, {vr(i + j)}")
-        for j in range(8):
-            e.raw(f"v_mul_f32 {vr(S0 + j)}, {sr(S_CEXP)}, {vr(S0 + j)}")
-        for j in range(4):
-            e.raw(f"v_cvt_pk_bf16_f32 {vr(i + j)}, {vr(S0 + 2 * j)}, {vr(S0 + 1 + 2 * j)}")
     stat_publish(e, 0, 0, "stw")
     e.raw("s_waitcnt lgkmcnt(0)")
     e.ds = []
@@ -633,7 +622,7 @@ def generate():
 def main():
     e = generate()
     clob = [f"v{i}" for i in range(256) if not (IN_V <= i < IN_V + 16)] + [f"a{i}" for i in range(256)]
-    clob += [f"s{S_CEXP}"] + [f"s{i}" for i in range(64, 94)]
+    clob += [f"s{i}" for i in range(64, 94)]
     write_inc(sys.stdout, "gen_bwd_dkv_asm.py" + (" 64" if D == 64 else ""), "ST_DKV_FAST" + ("64" if D == 64 else ""), e,
               LDS_BYTES, clob)
 

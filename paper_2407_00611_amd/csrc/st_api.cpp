@@ -214,6 +214,38 @@ st_status st_profile_end(st_profile_entry* out, int32_t max_entries, int32_t* n_
   return status;
 }
 
+st_status st_mfma_probe(const void* operands, int64_t operand_bytes, int32_t iters, float* sink, int64_t sink_floats,
+                        double* flop, void* hip_stream) {
+  if (operands == nullptr || sink == nullptr) return fail(ST_ERR_INVALID_ARG, "null pointer");
+  if (reinterpret_cast<uintptr_t>(operands) % 16) return fail(ST_ERR_ALIGNMENT, "operands: not 16-byte aligned");
+  if (operand_bytes < 65536) return fail(ST_ERR_INVALID_ARG, "operands: at least 65536 bytes are needed");
+  if (iters < 1 || iters > (1 << 24)) return fail(ST_ERR_INVALID_ARG, "iters must be in 1 .. 2^24");
+  const int blocks = st::mfma_probe_blocks();
+  if (sink_floats < (int64_t)blocks * 256) return fail(ST_ERR_INVALID_ARG, "sink: %lld floats are needed", (long long)blocks * 256);
+  ST_HIP(st::launch_mfma_probe(operands, operand_bytes, iters, sink, blocks, (hipStream_t)hip_stream), "st_mfma_probe launch");
+  if (flop) *flop = st::mfma_probe_flop(blocks, iters);
+  return ST_OK;
+}
+
+st_status st_device_facts(st_device_report* out) {
+  if (out == nullptr) return fail(ST_ERR_INVALID_ARG, "null output");
+  memset(out, 0, sizeof(*out));
+  int dev = 0;
+  ST_HIP(hipGetDevice(&dev), "hipGetDevice");
+  hipDeviceProp_t prop;
+  ST_HIP(hipGetDeviceProperties(&prop, dev), "hipGetDeviceProperties");
+  const st::DeviceInfo& info = st::device_info();
+  out->compute_units = info.cus > 0 ? info.cus : prop.multiProcessorCount;
+  out->xcds = info.xcds;
+  out->max_clock_mhz = prop.clockRate / 1000;
+  out->memory_clock_mhz = prop.memoryClockRate / 1000;
+  out->memory_bus_bits = prop.memoryBusWidth;
+  out->hbm_bytes = (int64_t)prop.totalGlobalMem;
+  strncpy(out->name, prop.name, sizeof(out->name) - 1);
+  strncpy(out->arch, prop.gcnArchName, sizeof(out->arch) - 1);
+  return ST_OK;
+}
+
 const char* st_status_str(st_status s) {
   switch (s) {
     case ST_OK: return "ok";
@@ -317,9 +349,14 @@ st_status st_attn_delta(const st_block_desc* d, const st_tensor* d_o, const st_t
   return ST_OK;
 }
 
+size_t st_attn_block_bwd_workspace_bytes(const st_block_desc* d) {
+  if (d == nullptr || d->dtype != ST_BF16 || d->B <= 0 || d->Sq <= 0 || d->Hq <= 0 || d->D <= 0) return 0;
+  return align_up((size_t)d->B * d->Sq * d->Hq * d->D * 2, 256);     // Q' = bf16(Q scale log2 e)
+}
+
 st_status st_attn_block_bwd(const st_block_desc* d, const st_tensor* q, const st_tensor* k, const st_tensor* v,
                             const st_tensor* d_o, const float* lse_final, const float* delta, float* dq_acc,
-                            float* dk_acc, float* dv_acc, void* hip_stream) {
+                            float* dk_acc, float* dv_acc, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
   ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
   ST_TRY(check_scale(d->scale));
@@ -346,6 +383,12 @@ st_status st_attn_block_bwd(const st_block_desc* d, const st_tensor* q, const st
   a.t.ksb = k->stride_b; a.t.kss = k->stride_s; a.t.ksh = k->stride_h;
   a.t.vsb = v->stride_b; a.t.vss = v->stride_s; a.t.vsh = v->stride_h;
   a.lse = lse_final; a.delta = delta; a.dq = dq_acc; a.dk[0] = dk_acc; a.dv[0] = dv_acc;
+  if (d->dtype == ST_BF16 && workspace != nullptr) {
+    if (workspace_bytes < st_attn_block_bwd_workspace_bytes(d)) return fail(ST_ERR_WORKSPACE, "block backward workspace needs %zu bytes", st_attn_block_bwd_workspace_bytes(d));
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(ST_ERR_ALIGNMENT, "workspace: not 256-byte aligned");
+    ST_HIP(st::launch_scale_q(a.q, workspace, d->B, d->Sq, d->Hq, d->D, d->scale, (hipStream_t)hip_stream), "scaled-Q launch");
+    a.qs = workspace;
+  }
   ST_HIP(launch_bwd(d->dtype, a, (hipStream_t)hip_stream), "st_attn_block_bwd launch");
   return ST_OK;
 }
@@ -442,12 +485,14 @@ int fwd_splits(const st_ring_desc* d, int n_visible) {
 //   forward, stepwise: partial O, partial lse, member O, member lse
 //   forward, fused:    partial O and partial lse, once (when more than one launch is needed) or once per
 //                      split of an under-filled launch: [O_0, lse_0, O_1, lse_1, ...]
-//   backward:          Delta, then the tile counters of the dK/dV launch (kQueueInts ints)
+//   backward:          Delta, the tile counters of the dK/dV launch (kQueueInts ints), and for the bf16 dtype
+//                      Q' = bf16(Q scale log2 e), dense [B,Sq,Hq,D]
 size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t backward) {
   if (d == nullptr) return 0;
   const size_t n_o = align_up((size_t)d->B * d->Sq * d->Hq * d->D * sizeof(float), 256);
   const size_t n_l = align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256);
-  if (backward) return n_l + align_up(st::kQueueInts * sizeof(int32_t), 256);
+  if (backward)
+    return n_l + align_up(st::kQueueInts * sizeof(int32_t), 256) + (d->dtype == ST_BF16 ? align_up(n_o / 2, 256) : 0);
   if (mode == ST_RING_STEPWISE) return 2 * (n_o + n_l);
   // the split grows with the number of visited chunks up to one launch's table, and any subset may be visited
   const int n_most = d->n_chunks < st::kMaxTable ? d->n_chunks : st::kMaxTable;
@@ -646,6 +691,11 @@ st_status st_ring_bwd_last(const st_ring_desc* d, const st_tensor* q, const st_t
   set_table_strides(a.t, d);
   a.lse = lse_final; a.delta = delta; a.dq = dq_acc;
   a.queue = (int32_t*)((char*)workspace + align_up((size_t)d->B * d->Sq * d->Hq * sizeof(float), 256));
+  if (d->dtype == ST_BF16) {
+    void* qs = (char*)a.queue + align_up(st::kQueueInts * sizeof(int32_t), 256);
+    ST_HIP(st::launch_scale_q(a.q, qs, d->B, d->Sq, d->Hq, d->D, d->scale, stream), "scaled-Q launch");
+    a.qs = qs;
+  }
   const int per_launch = mode == ST_RING_FUSED ? st::kMaxTable : 1;
   for (int x0 = 0; x0 < n; x0 += per_launch) {
     const int cnt = n - x0 < per_launch ? n - x0 : per_launch;

@@ -24,6 +24,7 @@ namespace st {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ int visible_keys(int causal, int Sk, int64_t qpos, int64_t k0) {
   if (!causal) return Sk;
@@ -73,7 +74,7 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
     qpos[qb] = q_pos(s, i);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      qf[qb][ks] = global_frag(qbase, a.q.ss, i, s.Sq, ks, g);
+      qf[qb][ks] = scale_bf16x8(global_frag(qbase, a.q.ss, i, s.Sq, ks, g), s.scale * kLog2e);   // Q': scores in log2 units
       dof[qb][ks] = global_frag(dobase, a.d_o.ss, i, s.Sq, ks, g);
     }
     lse2[qb] = INFINITY;
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256, kQ_WQ == 32 ? 2 : 1) void bwd_dq_bf16_kernel(c
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[db][qb][v] = 0.f;
-  const float c_exp = s.scale * kLog2e;
+  constexpr float c_exp = 1.f;   // the Q operand is Q' = bf16(Q scale log2 e): the scores are exponents already
 
   auto chunk_tiles = [&](int c) -> int {
     const int nv = visible_keys(s.causal, s.Sk, q_pos(s, wg_last_row), a.t.k_offset[c]);
@@ -299,7 +300,7 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
         acc_k[db][nb][v] = 0.f;
         acc_v[db][nb][v] = 0.f;
       }
-  const float c_exp = s.scale * kLog2e;
+  constexpr float c_exp = 1.f;   // the Q operand is Q' = bf16(Q scale log2 e): the scores are exponents already
 
   // flattened (head of the group, query tile) walk
   const int n_head_lo = q_split - q_tile_first;
@@ -317,7 +318,11 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
     const int i0 = tile_of(step) * kK_BQ;
     const char* qb_ = (const char*)a.q.ptr + ((int64_t)b * a.q.sb + (int64_t)h * a.q.sh) * 2;
     const char* dob_ = (const char*)a.d_o.ptr + ((int64_t)b * a.d_o.sb + (int64_t)h * a.d_o.sh) * 2;
+    // the Q tile holds Q' = bf16(Q scale log2 e), converted here in the staging registers: the scores come out
+    // in log2 units, and dK^T = Q'^T dS carries a factor scale log2 e (the epilogue multiplies by ln 2, not by scale)
     stage_load<D, kK_BQ>(rq, qb_, a.q.ss, i0, s.Sq, tid);
+#pragma unroll
+    for (int j = 0; j < StageRegs<D, kK_BQ>::kN; ++j) rq.x[j] = scale_bf16x8(rq.x[j], s.scale * kLog2e);
     stage_load<D, kK_BQ>(rdo, dob_, a.d_o.ss, i0, s.Sq, tid);
     if (tid < 2 * kK_BQ) {
       const int row = i0 + (tid & (kK_BQ - 1));
@@ -426,7 +431,8 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
     buf ^= 1;
   }
 
-  // dk_acc += scale * dK, dv_acc += dV  (single owner of these key rows)
+  // dk_acc += scale * dS^T Q = ln 2 * dS^T Q' (Q' = Q scale log2 e), dv_acc += dV  (single owner of these key rows)
+  const float k_mul = kLn2;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int t = wave_key0 + 32 * nb + r;
@@ -440,10 +446,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(const BwdArgs a) {
         for (int q4 = 0; q4 < 4; ++q4) {
           const int d = 32 * db + 8 * q4 + 4 * g;
           float4 x = *reinterpret_cast<float4*>(dkr + d);
-          x.x += s.scale * acc_k[db][nb][4 * q4 + 0];
-          x.y += s.scale * acc_k[db][nb][4 * q4 + 1];
-          x.z += s.scale * acc_k[db][nb][4 * q4 + 2];
-          x.w += s.scale * acc_k[db][nb][4 * q4 + 3];
+          x.x += k_mul * acc_k[db][nb][4 * q4 + 0];
+          x.y += k_mul * acc_k[db][nb][4 * q4 + 1];
+          x.z += k_mul * acc_k[db][nb][4 * q4 + 2];
+          x.w += k_mul * acc_k[db][nb][4 * q4 + 3];
           *reinterpret_cast<float4*>(dkr + d) = x;
           float4 y = *reinterpret_cast<float4*>(dvr + d);
           y.x += acc_v[db][nb][4 * q4 + 0];
@@ -467,12 +473,7 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
   const int64_t total_k = (int64_t)n_kt * a.s.Hkv * a.s.B * a.t.n;
   if (total_q > 0x7fffffff || total_k > 0x7fffffff) return hipErrorInvalidValue;
   if (a.s.D != 128 && a.s.D != 64) return hipErrorInvalidValue;
-  // tuning / debugging override: ST_DKV_FAST=0 keeps all dK/dV work in the general kernel
-  static const int fast_env = [] {
-    const char* e = getenv("ST_DKV_FAST");
-    return e ? atoi(e) : 1;
-  }();
-  a.dkv_fast = (fast_env && dkv_fast_usable(a)) ? 1 : 0;
+  a.dkv_fast = (knobs().dkv_fast && dkv_fast_usable(a)) ? 1 : 0;
   if (a.s.causal) {
     // earlier chunks first (the backward does not depend on the order of the table): their keys are seen by
     // more query rows, and workgroups are handed out in table order
@@ -545,11 +546,7 @@ hipError_t launch_bwd_bf16(const BwdArgs& a_in, hipStream_t stream) {
     if (e == hipSuccess && cast_dv[c]) e = launch_cast(a.dv[c], cast_dv[c], n_kv, ST_BF16, stream);
     if (e != hipSuccess) return e;
   }
-  static const int dq_fast_env = [] {
-    const char* e = getenv("ST_DQ_FAST");
-    return e ? atoi(e) : 1;
-  }();
-  a.dq_fast = (dq_fast_env && dq_fast_usable(a)) ? 1 : 0;
+  a.dq_fast = (knobs().dq_fast && dq_fast_usable(a)) ? 1 : 0;
   {
     ProfScope prof(a.dq_fast ? "bwd_dq_edge" : "bwd_dq_bf16", stream);
     if (a.s.D == 128) hipLaunchKernelGGL(bwd_dq_bf16_kernel<128>, dim3((unsigned)total_q), dim3(256), 0, stream, a);

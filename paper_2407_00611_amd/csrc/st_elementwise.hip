@@ -3,6 +3,7 @@
 // fp32 -> storage-dtype casts and the (O = 0, lse = -inf) state fill.
 // One 16-byte vector per lane, rows never straddle a lane; grid sized to the data.
 #include "st_internal.h"
+#include "st_mfma.h"
 
 namespace st {
 namespace {
@@ -22,7 +23,7 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 // A row occupies a power-of-two group of lanes (lanes beyond vec_per_row idle), so a row never
 // straddles a wavefront: every lane of the row has read lse_acc before lane 0 overwrites it.
 // Weights: w_acc = exp(lse_acc - lse'), w_part = exp(lse_part - lse'), lse' = max + log(sum).
-// A side with lse = -inf gets weight 0 without ever forming (-inf) - (-inf).
+// A side with lse = -inf gets weight 0 without ever forming (-inf) - (-inf), and its O is not read into the sum.
 constexpr int kMergeUnroll = 4;   // vectors per thread: all loads of a thread are in flight before its first store
 
 template <bool kLowp>
@@ -69,11 +70,15 @@ __global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, f
       wa = ea * inv;
       wp = ep * inv;
     }
+    // a side whose weight is exactly 0 (an empty state) is left out, so that a non-finite value in its O
+    // (never written, or stale) cannot turn the result into NaN; the combine pass does the same
+    const float4 za = wa != 0.f ? a[u] : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 zp = wp != 0.f ? p[u] : make_float4(0.f, 0.f, 0.f, 0.f);
     float4 r;
-    r.x = wa * a[u].x + wp * p[u].x;
-    r.y = wa * a[u].y + wp * p[u].y;
-    r.z = wa * a[u].z + wp * p[u].z;
-    r.w = wa * a[u].w + wp * p[u].w;
+    r.x = wa * za.x + wp * zp.x;
+    r.y = wa * za.y + wp * zp.y;
+    r.z = wa * za.z + wp * zp.z;
+    r.w = wa * za.w + wp * zp.w;
     reinterpret_cast<float4*>(o_acc)[v[u]] = r;
     if (kLowp) o_lowp[v[u]] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
     if (first[u]) lse_acc[sidx[u]] = lnew;
@@ -206,6 +211,20 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float4* __restrict
   }
 }
 
+// ---- Q' = bf16(Q * c): thread = 8 elements (16 bytes) of one (b, i, h) row; dense output -----------------
+__global__ __launch_bounds__(256) void scale_q_kernel(View q, u32x4* __restrict__ dst, int32_t B, int32_t Sq,
+                                                      int32_t Hq, int32_t D, float c) {
+  const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int32_t per_row = D / 8;
+  const int64_t row = v / per_row;
+  if (row >= (int64_t)B * Sq * Hq) return;
+  const int32_t chunk = (int32_t)(v % per_row);
+  const int32_t h = (int32_t)(row % Hq);
+  const int64_t bi = row / Hq;
+  const int64_t off = (bi / Sq) * q.sb + (bi % Sq) * q.ss + (int64_t)h * q.sh + chunk * 8;
+  dst[v] = scale_bf16x8(*reinterpret_cast<const u32x4*>((const uint16_t*)q.ptr + off), c);
+}
+
 __global__ __launch_bounds__(256) void fill_state_kernel(float* __restrict__ o, float* __restrict__ lse,
                                                          int64_t n_o, int64_t n_lse) {
   const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -296,6 +315,16 @@ hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hi
   ProfScope prof("cast", s);
   hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n_vec + tail)), dim3(256), 0, s, (const float4*)src,
                      (uint2*)dst, n_vec, src + n_vec * 4, (uint16_t*)dst + n_vec * 4, tail);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_q(const View& q, void* dst, int32_t B, int32_t Sq, int32_t Hq, int32_t D, float scale,
+                          hipStream_t s) {
+  const int64_t n_vec = (int64_t)B * Sq * Hq * (D / 8);
+  if (n_vec == 0) return hipSuccess;
+  ProfScope prof("scale_q", s);
+  hipLaunchKernelGGL(scale_q_kernel, dim3(blocks_for(n_vec)), dim3(256), 0, s, q, (u32x4*)dst, B, Sq, Hq, D,
+                     scale * 1.4426950408889634f);
   return hipGetLastError();
 }
 

@@ -24,6 +24,7 @@ constexpr int kBN = 64;       // keys per tile
 #define ST_FWD_WQ 32
 #endif
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kRescaleGap = 8.f;   // log2 units
 
 // visible prefix of a chunk for a query at global position qpos
@@ -57,8 +58,10 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
   const int b = hb / s.Hq;
   const int hk = h / (s.Hq / s.Hkv);
 
-  // ---- Q fragments (B operand of S^T): query column r of block qb, d = 16 ks + 8 g .. +7
+  // ---- Q fragments (B operand of S^T): query column r of block qb, d = 16 ks + 8 g .. +7, as the exponent
+  // operand Q' = bf16(Q scale log2 e) that every bf16 kernel uses: the scores come out in log2 units
   const int q_row0 = qt * kBM + wave * kWQ;
+  const float q_mul = s.scale * kLog2e;
   bf16x8 qf[QB][KS];
   int64_t qpos[QB];
 #pragma unroll
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     const char* qrow = (const char*)a.q.ptr + ((int64_t)b * a.q.sb + (int64_t)i * a.q.ss + (int64_t)h * a.q.sh) * 2;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      if (i < s.Sq) qf[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + (16 * ks + 8 * g) * 2);
+      if (i < s.Sq) qf[qb][ks] = scale_bf16x8(*reinterpret_cast<const bf16x8*>(qrow + (16 * ks + 8 * g) * 2), q_mul);
       else qf[qb][ks] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
     }
   }
@@ -84,13 +87,13 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc_o[db][qb][v] = 0.f;
-  float m_run[QB], l_run[QB];   // running max (in units of raw scores) and this lane's partial row sum
+  float m_run[QB], l_run[QB];   // running max (log2 units, like the scores) and this lane's partial row sum
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m_run[qb] = -INFINITY;
     l_run[qb] = 0.f;
   }
-  const float c_exp = s.scale * kLog2e;
+  constexpr float c_exp = 1.f;   // the scores are exponents already
 
   // ---- flattened (chunk, tile) walk with one-tile lookahead
   // number of tiles the workgroup needs from chunk c: up to the last key its last row may see
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
       // Lazy rescale: the exponent reference m_run only moves when some row's tile maximum exceeds it
       // by more than kRescaleGap (log2 units), so p <= 2^kRescaleGap and the O accumulator is rescaled
       // rarely.  Exact in real arithmetic: O and l stay consistent with whatever reference is in use,
-      // and lse = m_run * scale + ln(l) at the end.  The rest of the tile exists twice (with and
+      // and lse = m_run ln 2 + ln(l) at the end.  The rest of the tile exists twice (with and
       // without the rescale) so that the common path carries the accumulators through untouched.
       auto rescale_rows = [&]() {
 #pragma unroll
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     n_cur = n_nxt;
   }
 
-  // ---- epilogue: O = acc / l, lse = m * scale + ln(l); folded into the fast kernel's partial result if there is one
+  // ---- epilogue: O = acc / l, lse = m ln 2 + ln(l); folded into the fast kernel's partial result if there is one
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = q_row0 + 32 * qb + r;
@@ -253,7 +256,7 @@ __global__ __launch_bounds__(256, kWQ == 32 ? 2 : 1) void fwd_bf16_kernel(const 
     if (i < s.Sq) {
       const int64_t orow = (((int64_t)b * s.Sq + i) * s.Hq + h) * D;
       const int64_t srow = ((int64_t)b * s.Hq + h) * s.Sq + i;
-      float lse_own = l > 0.f ? m_run[qb] * s.scale + logf(l) : -INFINITY;
+      float lse_own = l > 0.f ? m_run[qb] * kLn2 + logf(l) : -INFINITY;
       float w_own = inv, w_prev = 0.f;          // weights of this kernel's accumulator and of the stored partial O
       if (fast_wrote) {
         const float lse_prev = out_lse[srow];
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
     const int i = q_row0 + 32 * qb + r;
     qpos[qb] = q_pos(s, i);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = global_frag(qbase, a.q.ss, i, s.Sq, ks, g);
+    for (int ks = 0; ks < KS; ++ks) qf[qb][ks] = scale_bf16x8(global_frag(qbase, a.q.ss, i, s.Sq, ks, g), s.scale * kLog2e);
   }
   const int wg_last_row = min(qt * kBM + kBM, s.Sq) - 1;
   const int wave_first_row = q_row0;
@@ -351,7 +354,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc_o[db][qb][v] = 0.f;
   float m_run[QB] = {-INFINITY, -INFINITY}, l_run[QB] = {0.f, 0.f};
-  const float c_exp = s.scale * kLog2e;
+  constexpr float c_exp = 1.f;   // Q fragments are Q' = bf16(Q scale log2 e): the scores are exponents already
 
   // ---- tile walk: cursors for the tile in softmax / PV (cur), in S (nxt) and in flight by DMA (dma)
   auto chunk_tiles = [&](int c) -> int {
@@ -412,15 +415,9 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
       }
     }
     auto k_frag = [&](uint32_t ktile_addr, int kb, int ks) -> bf16x8 {
-#ifdef ST_ABL_NOLDSK
-      return __builtin_bit_cast(bf16x8, u32x4{ktile_addr, nat_off[ks], 3, 4});
-#endif
       return lds_read_b128((const ST_LDS char*)(uintptr_t)(ktile_addr + nat_off[ks]) + 32 * kb * ROWB);
     };
     auto v_frag = [&](uint32_t vtile_addr, int row0, int db) -> bf16x8 {     // row0 % 16 == 0
-#ifdef ST_ABL_NOLDSV
-      return __builtin_bit_cast(bf16x8, u32x4{vtile_addr, tr_lo[db], tr_hi[db], 4});
-#endif
       const u32x2 lo = lds_read_tr16((const ST_LDS char*)(uintptr_t)(vtile_addr + tr_lo[db]) + row0 * ROWB);
       const u32x2 hi = lds_read_tr16((const ST_LDS char*)(uintptr_t)(vtile_addr + tr_hi[db]) + row0 * ROWB);
       return __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], hi[0], hi[1]});
@@ -501,9 +498,6 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[0][ks]), "+a"(qf[1][ks]));
       u32x4 pf[2][QB];   // P^T packed to bf16 per 16-key group m and query block
-#ifdef ST_ABL_NOEXP
-      for (int m = 0; m < 2; ++m) for (int qb = 0; qb < QB; ++qb) pf[m][qb] = u32x4{0x3c003c00u + (uint32_t)lane, 1, 2, 3};
-#endif
       float pv[32];   // exp results in flight between the slot that issues them and the slot that retires them
       // Element e of the exp stream: group m = e / 16, query block (e / 8) % 2, value j = e % 8.
       // A wavefront issues in order, so the use of a transcendental result right behind its v_exp
@@ -538,9 +532,6 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
       };
       // slot schedule: elements [lo(i), lo(i+1)) are issued in slot i and retired in slot i + 1
       auto exp_slot = [&](int lo_prev, int lo_cur, int lo_next) {
-#ifdef ST_ABL_NOEXP
-        return;
-#endif
         exp_issue(lo_cur, lo_next);
         // retire in pairs so that a bf16 pack always sees both halves
         exp_retire(lo_prev & ~1, lo_cur & ~1);
@@ -561,11 +552,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
       for (int i = 0; i < kS1; ++i) {
         const int ks = i / 2, qb = i % 2;
         if (qb == 0 && ks + 2 < KS) kf[(ks + 2) % 3] = k_frag(ktile_addr, kbn, ks + 2);
-#ifndef ST_ABL_NOMFMA
         sn[qb] = mfma32(kf[ks % 3], qf[qb][ks], sn[qb]);
-#else
-        sn[qb][0] += __builtin_bit_cast(u32x4, kf[ks % 3])[0] * 1e-30f;
-#endif
         ST_FENCE();
         exp_slot(i == 0 ? 0 : 20 * (i - 1) / kS1, 20 * i / kS1, 20 * (i + 1) / kS1);
         ST_FENCE();
@@ -585,18 +572,12 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
       for (int i = 0; i < kS2; ++i) {
         const int m = i / (2 * DB), db = (i / 2) % DB, qb = i % 2, f = i / 2;   // fragment f = m * DB + db
         if (qb == 0 && f + 2 < 2 * DB) vf[(f + 2) % 3] = v_frag(vtile_addr, 32 * kbc + 16 * ((f + 2) / DB), (f + 2) % DB);
-#ifndef ST_ABL_NOMFMA
         acc_o[db][qb] = mfma32(vf[f % 3], __builtin_bit_cast(bf16x8, pf[m][qb]), acc_o[db][qb]);
-#else
-        acc_o[db][qb][0] += __builtin_bit_cast(u32x4, vf[f % 3])[0] * 1e-30f + pf[m][qb][0] * 1e-30f;
-#endif
         ST_FENCE();
         if (i < kExp2) {
           exp_slot(i == 0 ? 20 * (kS1 - 1) / kS1 : 20 + 12 * (i - 1) / kExp2, 20 + 12 * i / kExp2, 20 + 12 * (i + 1) / kExp2);
         } else {
-#ifndef ST_ABL_NOEXP
           if (i == kExp2) exp_retire((20 + 12 * (kExp2 - 1) / kExp2) & ~1, 32);
-#endif
           // 16 pairs (8 per query block) of the next block's scores: to VGPRs, max3 per pair
           const int j = i - kExp2, n2 = kS2 - kExp2, per = (16 + n2 - 1) / n2;
 #pragma unroll
@@ -627,9 +608,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
     int stage = 0;   // LDS stage of the current tile; the next tile sits in stage + 1, the DMA goes to stage + 3
     while (true) {
       const bool have_dma = valid(dma);
-#ifndef ST_ABL_NODMA
       if (have_dma) issue_dma(dma, (stage + 3) & (NS - 1));
-#endif
       const uint32_t cur_addr = smem_addr + stage * kStage, nxt_addr = smem_addr + ((stage + 1) & (NS - 1)) * kStage;
       // blocks (cur,0) -> (cur,1) -> (nxt,0)
       half_iteration(sA, sB, cur_addr + kTile, 0, cur_addr, 1, cur, true);
@@ -637,9 +616,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
       // the tile after next must have landed before anyone reads it; only this iteration's DMA may be in flight
       if (have_dma) wait_vmcnt<kDmaPerTile>();
       else wait_vmcnt<0>();
-#ifndef ST_ABL_NOBARRIER
       __syncthreads();
-#endif
       stage = (stage + 1) & (NS - 1);
       cur = nxt;
       nxt = advance(nxt);
@@ -648,7 +625,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
     }
   }
 
-  // ---- epilogue: O = acc / l, lse = m * scale + ln(l)
+  // ---- epilogue: O = acc / l, lse = m ln 2 + ln(l)
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int i = q_row0 + 32 * qb + r;
@@ -672,7 +649,7 @@ __global__ __launch_bounds__(256, 1) void fwd_pipe_kernel(const FwdArgs a) {
             *reinterpret_cast<uint2*>((uint16_t*)a.o_lowp + orow + d) = w;
           }
         }
-      if (g == 0) a.lse[((int64_t)b * s.Hq + h) * s.Sq + i] = l > 0.f ? m_run[qb] * s.scale + logf(l) : -INFINITY;
+      if (g == 0) a.lse[((int64_t)b * s.Hq + h) * s.Sq + i] = l > 0.f ? m_run[qb] * kLn2 + logf(l) : -INFINITY;
     }
   }
 }
@@ -707,20 +684,8 @@ hipError_t launch_fwd_bf16_wq(const FwdArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_fwd_bf16(const FwdArgs& a_in, hipStream_t stream) {
-  // tuning override: ST_FWD_WQ=64 selects one wavefront per SIMD with 64 queries each
-  static const int wq = [] {
-    const char* e = getenv("ST_FWD_WQ");
-    return e ? atoi(e) : ST_FWD_WQ;
-  }();
-  static const int pipe = [] {
-    const char* e = getenv("ST_FWD_PIPE");
-    return e ? atoi(e) : 1;
-  }();
-  // tuning / debugging override: ST_FWD_FAST=0 keeps the whole walk in the general kernels
-  static const int fast_env = [] {
-    const char* e = getenv("ST_FWD_FAST");
-    return e ? atoi(e) : 1;
-  }();
+  // tuning switches (see Knobs): the general kernel's variant, and whether the hand-scheduled kernel takes part
+  const int wq = knobs().fwd_wq, pipe = knobs().fwd_pipe, fast_env = knobs().fwd_fast;
   if ((fast_env || a_in.n_split > 1) && fwd_fast_usable(a_in)) {
     // fully visible full tiles by the hand-scheduled kernel, then everything else (merged into its result)
     FwdArgs a = a_in;

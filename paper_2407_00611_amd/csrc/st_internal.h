@@ -76,6 +76,9 @@ __host__ __device__ inline void split_range(int n, int n_split, int y, int& lo, 
 struct BwdArgs {
   Shape s;
   View q, d_o;
+  const void* qs;      // bf16 path: Q' = bf16(Q * scale * log2 e), the exponent operand (see scale_bf16x8), dense
+                       // [B,Sq,Hq,D], made by launch_scale_q; nullable: without it the key-stationary pass stays in
+                       // the general kernel, which converts the rows it stages itself
   ChunkTable t;
   const float* lse;    // final
   const float* delta;
@@ -92,8 +95,9 @@ struct BwdArgs {
   void* dv_lowp[kMaxTable];
   int32_t* queue;      // nullable, kQueueInts ints of device memory: the fast dK/dV kernel hands its key tiles out
                        // through it (one counter per XCD), so that XCDs that run faster take more of them
+  int32_t queue_xcds;  // counters in use (the device's XCD count, 1 .. 8); set by the launcher
 };
-constexpr int kQueueInts = 8 * 32;   // 8 counters, 128 bytes apart
+constexpr int kQueueInts = 8 * 32;   // at most 8 counters, 128 bytes apart
 // passed by value: the kernel-argument segment holds 4096 bytes, 256 of them the implicit arguments
 static_assert(sizeof(BwdArgs) <= 4096 - 256 && sizeof(FwdArgs) <= 4096 - 256, "argument structs must fit the kernel-argument segment");
 
@@ -130,6 +134,29 @@ __host__ __device__ inline bool dkv_chunk_fast_only(const Shape& s, int64_t k0) 
   const int r_any = q_row_of(s, k0), r_all = q_row_of(s, k0 + s.Sk - 1);
   return r_any == r_all && r_all % kDkvFastRows == 0 && r_all < s.Sq;
 }
+
+// Tuning and testing switches of the launchers.  The defaults are the product.  They are read from the
+// environment ONCE, when the library is loaded (ST_FWD_FAST, ST_DQ_FAST, ST_DKV_FAST, ST_DKV_QUEUE, ST_FWD_WQ,
+// ST_FWD_PIPE, ST_FWD_GAP); afterwards only st_testing_set() changes them, an exported entry point for the
+// library's own tests that the public header does not declare.  No launcher reads the environment.
+struct Knobs {
+  int fwd_fast = 1;    // 0: the forward stays in the general kernels
+  int dq_fast = 1;     // 0: the dQ pass stays in the general kernel
+  int dkv_fast = 1;    // 0: the dK/dV pass stays in the general kernel
+  int dkv_queue = 1;   // 0: every dK/dV key tile is a workgroup of its own (no tile queue)
+  int fwd_wq = 32;     // general forward without the fast path: queries per wavefront (32 or 64)
+  int fwd_pipe = 1;    // general forward without the fast path, head size 128: the pipelined variant
+  float fwd_gap = 8.f; // fast forward: log2 units a block maximum may exceed the lazy exponent reference by (0 .. 64)
+};
+Knobs& knobs();
+
+// Facts about a device that the launchers need, queried once per device and cached.
+constexpr int kMaxXcds = 8;
+struct DeviceInfo {
+  int cus = 0;         // compute units
+  int xcds = kMaxXcds; // accelerator complex dies (each with its own L2); kMaxXcds when the runtime does not tell
+};
+const DeviceInfo& device_info();   // of the current device
 
 // Optional per-kernel timing (st_profile_begin / st_profile_end): while enabled, a ProfScope
 // records a HIP event on the launch stream before and after the kernel it brackets.
@@ -178,7 +205,13 @@ hipError_t launch_combine(const CombineArgs& a, int lowp_dtype, hipStream_t s);
 hipError_t launch_delta(const View& d_o, int d_o_dtype, const View& o, int o_dtype, float* delta,
                         int32_t B, int32_t Sq, int32_t Hq, int32_t D, hipStream_t s);
 hipError_t launch_cast(const float* src, void* dst, int64_t n, int dst_dtype, hipStream_t s);
+// dst (dense bf16 [B,Sq,Hq,D]) = bf16(q * scale * log2 e) of a bf16 view q
+hipError_t launch_scale_q(const View& q, void* dst, int32_t B, int32_t Sq, int32_t Hq, int32_t D, float scale, hipStream_t s);
 hipError_t launch_fill_state(float* o, float* lse, int64_t n_o, int64_t n_lse, hipStream_t s);
 hipError_t launch_zero(void* dst, int64_t bytes, hipStream_t s);   // bytes % 4 == 0, dst 4-byte aligned
+// benchmark aid: MFMA-only loop, one workgroup per compute unit (see st_probe.hip)
+int mfma_probe_blocks();
+double mfma_probe_flop(int blocks, int32_t iters);
+hipError_t launch_mfma_probe(const void* operands, int64_t operand_bytes, int32_t iters, float* sink, int blocks, hipStream_t s);
 
 }  // namespace st

@@ -37,6 +37,21 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
+// Eight bf16 values times c, rounded to bf16 again (round to nearest even).  Every bf16 kernel of the path
+// evaluates its scores from the SAME exponent operand Q' = bf16(Q * scale * log2 e) (the MFMA then delivers
+// exponents in log2 units and no per-score multiply is needed), so forward and backward agree on every score:
+// the probabilities the backward recomputes sum to one over a row, whichever kernel computed which tile.
+__device__ __forceinline__ u32x4 scale_bf16x8(u32x4 x, float c) {
+  u32x4 y;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    y[j] = pack_bf16(__uint_as_float(x[j] << 16) * c, __uint_as_float(x[j] & 0xffff0000u) * c);
+  return y;
+}
+__device__ __forceinline__ bf16x8 scale_bf16x8(bf16x8 x, float c) {
+  return __builtin_bit_cast(bf16x8, scale_bf16x8(__builtin_bit_cast(u32x4, x), c));
+}
+
 // Eight consecutive C-layout values (v = 8m .. 8m+7) as a B (or A) operand.
 // Slot e of the operand then stands for row 16m + 8*(e/4) + 4g + e%4 of the C tile.
 __device__ __forceinline__ bf16x8 pack_c_as_b(const f32x16& c, int m) {
@@ -276,10 +291,13 @@ __device__ __forceinline__ void scale_in_place(f32x16& x, float a) {
 __device__ __forceinline__ float xhalf_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
 __device__ __forceinline__ float xhalf_sum(float x) { return x + __shfl_xor(x, 32); }
 
-// XCD-aware block order: consecutive hardware block ids land on different XCDs (8 of them, each with
-// its own L2), so give every XCD a contiguous range of logical tiles.
+// XCD-aware block order: consecutive hardware block ids land on different XCDs (kDispatchXcds of them on the
+// MI355X, each with its own L2), so give every XCD a contiguous range of logical tiles.  The count only shapes
+// the order in which work is handed out: on a device with another count every tile is still computed exactly
+// once, and only L2 locality is lost.
+constexpr int kDispatchXcds = 8;
 __device__ __forceinline__ int xcd_logical_block(int id, int total) {
-  return (total % 8 == 0) ? (id % 8) * (total / 8) + id / 8 : id;
+  return (total % kDispatchXcds == 0) ? (id % kDispatchXcds) * (total / kDispatchXcds) + id / kDispatchXcds : id;
 }
 
 // Block id -> (query tile, head-and-batch index) for the query-stationary kernels.  Every XCD gets a
@@ -289,9 +307,9 @@ __device__ __forceinline__ int xcd_logical_block(int id, int total) {
 __device__ __forceinline__ void qtile_block(int id, int total, int n_qt, int causal, int& qt, int& hb) {
   const int n_hb = total / n_qt;
   int qi;
-  if (n_hb % 8 == 0) {
-    const int per = n_hb / 8, j = id / 8;
-    hb = (id % 8) * per + j % per;
+  if (n_hb % kDispatchXcds == 0) {
+    const int per = n_hb / kDispatchXcds, j = id / kDispatchXcds;
+    hb = (id % kDispatchXcds) * per + j % per;
     qi = j / per;
   } else {
     hb = id % n_hb;

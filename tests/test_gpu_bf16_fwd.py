@@ -7,7 +7,7 @@ import torch
 import paper_2407_00611_amd as st
 import synth_inputs as si
 from oracle import attention as oa
-from util import assert_close, host, positions, upload
+from util import assert_close, assert_close_wide, host, launcher_switch, positions, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -51,9 +51,10 @@ def test_ring_forward_rising_maxima(D):
     for order in ([0, 1, 2, 3, 4], [4, 0, 3, 1, 2]):
         print(f"[fast_rescale] order {order}", flush=True)
         o, lse, o_low = st.st_ring_fwd(q, ks, vs, w.q_offset, koffs, w.causal, w.scale, order, None, st.ST_RING_FUSED)
-        assert_close(host(o), o_ref, "bf16", "o")
-        assert_close(host(lse), lse_ref, "bf16", "lse", lse=True)
-        assert_close(host(o_low), o_ref, "bf16", "o bf16")
+        # the last chunk's keys are five times the first one's: scores spread over some 7 log2 units (one sigma)
+        assert_close_wide(host(o), o_ref, "o")
+        assert_close_wide(host(lse), lse_ref, "lse", lse=True)
+        assert_close_wide(host(o_low), o_ref, "o bf16")
 
 
 @pytest.mark.parametrize("case", STEP_CASES, ids=[c[0] for c in STEP_CASES])
@@ -168,11 +169,15 @@ def test_many_chunks_forward_and_backward(case):
 
 @pytest.mark.parametrize("gap", ["0", "0.5", "2"])
 @pytest.mark.parametrize("D", [128, 64])
-def test_forward_with_a_tight_exponent_reference(D, gap, monkeypatch):
-    """ST_FWD_GAP (a testing override of the hand-scheduled loop) lets a block maximum exceed the lazy exponent
-    reference by only `gap` log2 units, so the rescale routine runs in most blocks of the walk (both score
-    buffers, the last tile's blocks, several times per row) instead of a few times per kernel."""
-    monkeypatch.setenv("ST_FWD_GAP", gap)
+def test_forward_with_a_tight_exponent_reference(D, gap):
+    """The launcher switch "fwd_gap" (a testing override of the hand-scheduled loop) lets a block maximum exceed
+    the lazy exponent reference by only `gap` log2 units, so the rescale routine runs in most blocks of the walk
+    (both score buffers, the last tile's blocks, several times per row) instead of a few times per kernel."""
+    with launcher_switch("fwd_gap", float(gap), 8.0):
+        _tight_reference_case(D, gap)
+
+
+def _tight_reference_case(D, gap):
     w = si.Workload("fast_tight_reference", 87, "bf16", 1, 2, 1, D, 512, 192, 6, 6 * 192 - 512, True, False, k_ramp=0.4)
     inp = si.make_inputs(w)
     q, ks, vs, _ = upload(inp)

@@ -143,3 +143,28 @@ def test_merge_lowp_output_and_cast():
     assert torch.equal(low, oa_.to(torch.bfloat16))               # RNE, same as torch's conversion
     x = torch.randn(1003, device="cuda")
     assert torch.equal(st.st_cast_from_f32(x, st.ST_BF16), x.to(torch.bfloat16))
+
+
+def test_merge_ignores_the_o_of_an_empty_state():
+    """A state with lse = -inf is the neutral element whatever its O holds (never written, stale, NaN): the
+    fold returns the other state.  Reference: the oracle's merge with the empty rows' O set to the neutral 0."""
+    torch.manual_seed(1)
+    B, Sq, Hq, D = 2, 37, 3, 64
+    o_a, o_b = torch.randn(B, Sq, Hq, D, device="cuda"), torch.randn(B, Sq, Hq, D, device="cuda")
+    l_a, l_b = torch.randn(B, Hq, Sq, device="cuda"), torch.randn(B, Hq, Sq, device="cuda")
+    l_a[0, 0, :9] = -float("inf")        # empty on the accumulator side
+    l_b[1, 2, 5:20] = -float("inf")      # empty on the partial side
+    l_a[1, 1, 30:] = -float("inf")       # empty on both sides
+    l_b[1, 1, 30:] = -float("inf")
+    ref_a, ref_b = host(o_a), host(o_b)
+    ref_a[np.isneginf(host(l_a)).transpose(0, 2, 1)] = 0.0
+    ref_b[np.isneginf(host(l_b)).transpose(0, 2, 1)] = 0.0
+    ref_o, ref_l = oa.merge(ref_a, host(l_a), ref_b, host(l_b))
+    o_a[torch.isneginf(l_a).transpose(1, 2)] = float("nan")
+    o_b[torch.isneginf(l_b).transpose(1, 2)] = float("inf")
+    low = torch.empty(B, Sq, Hq, D, device="cuda", dtype=torch.bfloat16)
+    st.st_attn_merge(o_a, l_a, o_b, l_b, st.ST_BF16, low)
+    assert_close(host(o_a), ref_o, "f32", "merge o")
+    assert_close(host(l_a), ref_l, "f32", "merge lse")
+    assert not o_a[1, 30:, 1].any()      # empty on both sides: O = 0
+    assert torch.equal(low, o_a.to(torch.bfloat16))

@@ -2,6 +2,9 @@
 tolerance checks the benchmark contract states."""
 from __future__ import annotations
 
+import contextlib
+import ctypes
+
 import numpy as np
 import torch
 
@@ -71,3 +74,46 @@ def assert_close(x, ref, dtype: str, what: str = "", lse: bool = False):
         assert err.max(initial=0.0) <= 2e-2, f"{what}: max abs err {err.max():.3e} > 2e-2"
         if not lse:
             assert fro <= 1e-2 * fro_ref + 1e-6 * np.sqrt(x.size), f"{what}: rel Frobenius {fro / max(fro_ref, 1e-300):.3e} > 1e-2"
+
+
+@contextlib.contextmanager
+def launcher_switch(name: str, value: float, default: float):
+    """Sets one launcher switch of the loaded library for the duration of a test (st_testing_set is exported
+    for the library's own tests and is not part of the public header), then puts the default back."""
+    import paper_2407_00611_amd as st
+    lib = ctypes.CDLL(st.library_path())
+    lib.st_testing_set.restype, lib.st_testing_set.argtypes = ctypes.c_int, [ctypes.c_char_p, ctypes.c_double]
+    assert lib.st_testing_set(name.encode(), float(value)) == 0, f"st_testing_set({name}, {value}) refused"
+    try:
+        yield
+    finally:
+        assert lib.st_testing_set(name.encode(), float(default)) == 0
+
+
+def assert_close_wide(x, ref, what: str = "", lse: bool = False):
+    """The bf16 bounds for inputs far from unit scale (peaked softmax: scores spread over ten and more log2 units,
+    gradients and lse well above 1).  The benchmark states max|x-ref| <= 2e-2 for unit-scale data; P, dS and the
+    query operand of the scores are each rounded to bf16 once (2^-9 relative), so an absolute error below the
+    bf16 resolution of the result itself cannot be asked for.  The absolute bound is therefore taken relative to
+    the largest reference value once that exceeds 1 (lse: 2.5e-3 of the largest |lse| once that exceeds 8, the
+    scores carrying one bf16 rounding of relative size 2^-9); the relative Frobenius bound of 1e-2 stands as it is.
+    Returns (max error / bound scale, relative Frobenius error)."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert x.shape == ref.shape, f"{what}: shape {x.shape} vs {ref.shape}"
+    inf_ref = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(x), inf_ref), f"{what}: -inf pattern differs"
+    assert not np.isnan(x).any(), f"{what}: NaN in result"
+    x = np.where(inf_ref, 0.0, x)
+    ref = np.where(inf_ref, 0.0, ref)
+    err = float(np.abs(x - ref).max(initial=0.0))
+    top = float(np.abs(ref).max(initial=0.0))
+    if lse:
+        bound = max(2e-2, 2.5e-3 * top)
+        assert err <= bound, f"{what}: max abs err {err:.3e} > {bound:.3e}"
+        return err / bound, 0.0
+    bound = 2e-2 * max(1.0, top)
+    fro = float(np.linalg.norm(x - ref)) / max(float(np.linalg.norm(ref)), 1e-30)
+    assert err <= bound, f"{what}: max abs err {err:.3e} > 2e-2 x {max(1.0, top):.2f}"
+    assert fro <= 1e-2, f"{what}: rel Frobenius {fro:.3e} > 1e-2"
+    return err / max(1.0, top), fro
