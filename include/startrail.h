@@ -250,6 +250,21 @@ st_status st_ring_bwd(const st_ring_desc* desc, const st_tensor* q, const st_ten
                       float* dq_acc, float* const* dk_acc, float* const* dv_acc,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* st_ring_bwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * st_ring_bwd (bit for bit) without the workspace: Delta, the tile counters of the dK/dV launch and the scaled
+ * copy of Q live in a static device array of st_ring_bwd_noalloc_max_bytes() = 40 MiB that every GPU the library
+ * runs on holds until the process ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no
+ * allocating library routine); the array's device address is looked up once per device, on the first call.
+ * A share whose st_ring_workspace_bytes(desc, mode, 1) exceeds the array returns ST_ERR_WORKSPACE and enqueues
+ * nothing.  Every call on a GPU uses that GPU's one array (what must start at zero is cleared by the call
+ * itself): calls that overlap on one GPU, on different streams or from different threads, race; order them. */
+st_status st_ring_bwd_noalloc(const st_ring_desc* desc, const st_tensor* q, const st_tensor* d_o,
+                              const st_tensor* o, int32_t o_dtype, const float* lse_final,
+                              const int32_t* order, int32_t n_visit, int32_t mode,
+                              float* dq_acc, float* const* dk_acc, float* const* dv_acc, void* hip_stream);
+size_t st_ring_bwd_noalloc_max_bytes(void);
+
 /* st_ring_bwd for the LAST visit of the listed chunks, with the work that follows a chunk's last visit folded
  * into the kernels that produce dK / dV (Section 3.2 "Backward Propagation": the key and value gradients are
  * complete once the chunk has met every query shard).

@@ -92,6 +92,9 @@ def _load() -> C.CDLL:
         "st_ring_fwd": (C.c_int, [R, T, i32p, i32p, C.c_int32, C.c_int32, f32p, f32p, vp, vp, C.c_size_t, vp]),
         "st_ring_bwd": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
+        "st_ring_bwd_noalloc": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
+                                          C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp]),
+        "st_ring_bwd_noalloc_max_bytes": (C.c_size_t, []),
         "st_ring_bwd_last": (C.c_int, [R, T, T, T, C.c_int32, f32p, i32p, C.c_int32, C.c_int32, f32p,
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
@@ -111,7 +114,7 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_combine", "st_attn_delta", "st_attn_block_bwd", "st_attn_block_bwd_workspace_bytes", "st_cast_from_f32",
-           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_last", "st_device_facts", "st_mfma_probe", "st_profile_begin",
+           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_noalloc", "st_ring_bwd_noalloc_max_bytes", "st_ring_bwd_last", "st_device_facts", "st_mfma_probe", "st_profile_begin",
            "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
@@ -427,6 +430,31 @@ def st_ring_bwd(q, k_chunks, v_chunks, d_o, o, lse_final, q_offset: int, k_offse
                             _i32_array(order), len(order), mode, _ptr(dq_acc),
                             C.cast(dk_ptr, C.POINTER(C.c_void_p)), C.cast(dv_ptr, C.POINTER(C.c_void_p)),
                             C.c_void_p(ws_ptr), ws_bytes, _stream(stream)), "st_ring_bwd")
+
+
+def st_ring_bwd_noalloc_max_bytes() -> int:
+    return int(_lib.st_ring_bwd_noalloc_max_bytes())
+
+
+def st_ring_bwd_noalloc(q, k_chunks, v_chunks, d_o, o, lse_final, q_offset: int, k_offsets: Sequence[int], causal: bool,
+                        scale: float, order: Sequence[int], dq_acc, dk_acc: Sequence[Optional[torch.Tensor]],
+                        dv_acc: Sequence[Optional[torch.Tensor]], mode: int = ST_RING_FUSED, stream=None) -> None:
+    """st_ring_bwd on the library's static scratch: this wrapper allocates no device memory either."""
+    B, Sq, Hq, D = q.shape
+    r = _Ring(q, k_chunks, v_chunks, q_offset, k_offsets, causal, scale)
+    n = len(k_chunks)
+    _f32_dense(dq_acc, (B, Sq, Hq, D), "dq_acc"); _f32_dense(lse_final, (B, Hq, Sq), "lse_final")
+    kv_shape = tuple(k_chunks[0].shape)
+    for t in list(dk_acc) + list(dv_acc):
+        if t is not None:
+            _f32_dense(t, kv_shape, "dk_acc/dv_acc entry")
+    dk_ptr = (C.c_void_p * n)(*[(t.data_ptr() if t is not None else None) for t in dk_acc])
+    dv_ptr = (C.c_void_p * n)(*[(t.data_ptr() if t is not None else None) for t in dv_acc])
+    tq, td, to = _view(q), _view(d_o), _view(o)
+    _check(_lib.st_ring_bwd_noalloc(C.byref(r.desc), C.byref(tq), C.byref(td), C.byref(to), _dtype_code(o),
+                                    _ptr(lse_final), _i32_array(order), len(order), mode, _ptr(dq_acc),
+                                    C.cast(dk_ptr, C.POINTER(C.c_void_p)), C.cast(dv_ptr, C.POINTER(C.c_void_p)),
+                                    _stream(stream)), "st_ring_bwd_noalloc")
 
 
 def st_ring_bwd_last(q, k_chunks, v_chunks, d_o, o, lse_final, q_offset: int, k_offsets: Sequence[int], causal: bool,

@@ -24,6 +24,15 @@ constexpr size_t kProfMax = 4096;
 
 thread_local char g_err[512] = "";
 
+// ---- scratch of st_ring_bwd_noalloc: device memory every loaded GPU holds until the process ends ----
+// In host code the array's name is only a handle: its device address differs from GPU to GPU and is looked up
+// once per device with hipGetSymbolAddress (scratch_of_current_device); kernels only ever see that pointer.
+constexpr size_t kScratchBytes = (size_t)40 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kScratchDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kScratchDevices];
+
 st_status fail(st_status s, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -34,6 +43,24 @@ st_status fail(st_status s, const char* fmt, ...) {
 
 st_status hip_fail(hipError_t e, const char* what) {
   return fail(ST_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Device address of `scratch` on the current device (looked up on the first call per device, then cached).
+st_status scratch_of_current_device(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kScratchDevices) return fail(ST_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kScratchDevices - 1);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (p == nullptr || reinterpret_cast<uintptr_t>(p) % 256) return fail(ST_ERR_HIP, "scratch symbol has no aligned device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ST_OK;
 }
 
 inline size_t elem_size(int dtype) { return dtype == ST_BF16 ? 2 : 4; }
@@ -622,6 +649,22 @@ st_status st_ring_bwd(const st_ring_desc* d, const st_tensor* q, const st_tensor
   return st_ring_bwd_last(d, q, d_o, o, o_dtype, lse_final, order, n_visit, mode, dq_acc, dk_acc, dv_acc, 0, nullptr,
                           nullptr, workspace, workspace_bytes, hip_stream);
 }
+
+st_status st_ring_bwd_noalloc(const st_ring_desc* d, const st_tensor* q, const st_tensor* d_o, const st_tensor* o,
+                              int32_t o_dtype, const float* lse_final, const int32_t* order, int32_t n_visit,
+                              int32_t mode, float* dq_acc, float* const* dk_acc, float* const* dv_acc, void* hip_stream) {
+  if (d == nullptr) return fail(ST_ERR_INVALID_ARG, "null descriptor");
+  ST_TRY(check_shape(d->dtype, d->B, d->Hq, d->Hkv, d->D, d->Sq, d->Sk));
+  const size_t need = st_ring_workspace_bytes(d, mode, 1);
+  if (need > kScratchBytes)
+    return fail(ST_ERR_WORKSPACE, "st_ring_bwd_noalloc: this share needs %zu bytes of scratch, the library's static scratch holds %zu; use st_ring_bwd with a workspace", need, kScratchBytes);
+  void* ws = nullptr;
+  ST_TRY(scratch_of_current_device(&ws));
+  return st_ring_bwd_last(d, q, d_o, o, o_dtype, lse_final, order, n_visit, mode, dq_acc, dk_acc, dv_acc, 0, nullptr,
+                          nullptr, ws, kScratchBytes, hip_stream);
+}
+
+size_t st_ring_bwd_noalloc_max_bytes(void) { return kScratchBytes; }
 
 st_status st_ring_bwd_last(const st_ring_desc* d, const st_tensor* q, const st_tensor* d_o, const st_tensor* o,
                            int32_t o_dtype, const float* lse_final, const int32_t* order, int32_t n_visit,
