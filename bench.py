@@ -139,6 +139,9 @@ def main() -> int:
                          "zigzag: the model of configuration 4 under the load-balanced causal placement (--rank picks the rank)")
     ap.add_argument("--rank", type=int, default=0, help="rank of the ring for --shape zigzag (0..31)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
+                    help="replay the step from a HIP graph instead of launching its kernels one by one; auto: only for "
+                         "launch-bound workloads (less than 0.1 TFLOP per step: configurations 1 and 2)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures ONE GPU's share of the ring; runs with more than one GPU are not part of "
@@ -258,6 +261,21 @@ def main() -> int:
             st.st_cast_from_f32(dq, storage, dq_low)
 
     step = step_team if team else step_ring
+    fwd_flop, bwd_flop = si.algorithmic_flop(w, order if team else None)
+    use_graph = args.graph == "on" or (args.graph == "auto" and fwd_flop + bwd_flop < 1e11)
+    if use_graph:
+        # a launch-bound step (a handful of kernels of some 10 us each) is captured once and replayed: the
+        # library only enqueues kernels on the given stream, so the captured graph is the whole step
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                   # one-time set-up (device facts) happens outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        eager_step, step = step, graph.replay
 
     for _ in range(args.warmup):
         step()
@@ -280,11 +298,10 @@ def main() -> int:
     torch.cuda.synchronize()
     st.st_profile_begin()
     for _ in range(prof_steps):
-        step()
+        (eager_step if use_graph else step)()              # the profiling events are not part of a captured graph
     kernels = st.st_profile_end()
 
     met = order if team else None                          # chunks that earn FLOP (ring shape: all of them)
-    fwd_flop, bwd_flop = si.algorithmic_flop(w, met)
     total_flop = fwd_flop + bwd_flop
     value = total_flop / (ms_per_step * 1e-3) / 1e12
     pairs = si.visible_pairs(w, met) * w.Hq * w.B
@@ -328,7 +345,7 @@ def main() -> int:
                    "n_chunks": w.n_chunks, "causal": w.causal, "q_offset": w.q_offset, "q_seg": w.q_seg, "q_offset2": w.q_offset2, "mode": args.mode,
                    "shape": args.shape,
                    "visit_order": f"P={w.ring_P},C={w.ring_C},rank={w.ring_rank}" if w.ring_P else "natural",
-                   "passes": "fwd+bwd" if w.backward else "fwd"},
+                   "passes": "fwd+bwd" if w.backward else "fwd", "launch": "hip_graph_replay" if use_graph else "eager"},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "device": {"name": facts["name"], "arch": facts["arch"], "cus": facts["compute_units"], "xcds": facts["xcds"],
                    "max_clock_mhz": facts["max_clock_mhz"], "memory_clock_mhz": facts["memory_clock_mhz"],

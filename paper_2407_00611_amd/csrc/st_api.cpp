@@ -511,7 +511,7 @@ int fwd_splits(const st_ring_desc* d, int n_visible) {
 // Workspace layout (each block 256-byte aligned):
 //   forward, stepwise: partial O, partial lse, member O, member lse
 //   forward, fused:    partial O and partial lse, once (when more than one launch is needed) or once per
-//                      split of an under-filled launch: [O_0, lse_0, O_1, lse_1, ...]
+//                      split of an under-filled launch plus one for its masked / ragged tiles: [O_0, lse_0, O_1, ...]
 //   backward:          Delta, the tile counters of the dK/dV launch (kQueueInts ints), and for the bf16 dtype
 //                      Q' = bf16(Q scale log2 e), dense [B,Sq,Hq,D]
 size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t backward) {
@@ -523,7 +523,8 @@ size_t st_ring_workspace_bytes(const st_ring_desc* d, int32_t mode, int32_t back
   if (mode == ST_RING_STEPWISE) return 2 * (n_o + n_l);
   // the split grows with the number of visited chunks up to one launch's table, and any subset may be visited
   const int n_most = d->n_chunks < st::kMaxTable ? d->n_chunks : st::kMaxTable;
-  return (size_t)fwd_splits(d, n_most) * (n_o + n_l);
+  const int splits = fwd_splits(d, n_most);
+  return (size_t)(splits > 1 ? splits + 1 : 1) * (n_o + n_l);
 }
 
 st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* order, const int32_t* member_of,
@@ -579,8 +580,8 @@ st_status st_ring_fwd(const st_ring_desc* d, const st_tensor* q, const int32_t* 
     ST_HIP(launch_fwd(d->dtype, a, stream), "split forward launch");
     st::CombineArgs c;
     memset(&c, 0, sizeof(c));
-    c.n = splits;
-    for (int y = 0; y < splits; ++y) {
+    c.n = splits + 1;                               // one state per split, and the general workgroups' own
+    for (int y = 0; y < splits + 1; ++y) {
       c.o[y] = part_o + (int64_t)y * a.split_o;
       c.lse[y] = part_l + (int64_t)y * a.split_l;
     }

@@ -58,6 +58,7 @@ struct FwdArgs {
   float* lse;      // fp32 [B,Hq,Sq]
   void* o_lowp;    // nullable, [B,Sq,Hq,D] in the storage dtype
   int32_t fwd_fast;  // 1: the fast forward kernel ran first and owns the tiles qtile_fast_tiles describes
+                     // 2: it owns them and runs in the same launch; the general workgroups write state n_split
   // Under-filled launches: n_split > 1 gives every query tile n_split workgroups (blockIdx.y), each walking a
   // contiguous share of the table and writing its own partial state at o + y * split_o, lse + y * split_l
   // (floats); the states are combined afterwards.  0 or 1: one workgroup walks the whole table.
@@ -192,6 +193,8 @@ hipError_t launch_bwd_f32(const BwdArgs& a, hipStream_t s);
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
 bool fwd_fast_usable(const FwdArgs& a);
 hipError_t launch_fwd_fast(const FwdArgs& a, hipStream_t s);
+// split launches (a.n_split > 1): fast and general workgroups in one launch, n_split + 1 partial states
+hipError_t launch_fwd_side_by_side(const FwdArgs& a, hipStream_t s);
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
 bool dkv_fast_usable(const BwdArgs& a);
 hipError_t launch_bwd_dkv_fast(const BwdArgs& a, hipStream_t s);

@@ -129,7 +129,7 @@ def test_forward_workspace_covers_every_visited_subset():
         return st.st_ring_workspace_bytes(q, ks, ks, 0, [Sk * j for j in range(n_chunks)], True, 0.1, st.ST_RING_FUSED, False)
 
     one = need(1)
-    assert one > 0 and need(2) == 2 * one                    # two chunks: two partial states
+    assert one > 0 and need(2) == 3 * one                    # two chunks: a state per split and the general workgroups' own
     sizes = [need(n) for n in (1, 2, 5, 16, 50, 64)]
     assert sizes == sorted(sizes)                             # grows with the table ...
     assert need(150) == need(64) == need(256)                 # ... up to one launch's table, and stays there
