@@ -23,7 +23,12 @@ to the general kernel).  Per block and wavefront, with the MFMA C layout "lane =
               VALU: dS = P dP', bf16 pack (in place)                   (runs under phase 3 / 4 MFMAs)
     phase 4   dK^T += Q'^T dS                   A: Q'^T by LDS transpose reads, B: packed dS  (the epilogue's factor is
                                                 ln 2 = scale / (scale log2 e) where dK = scale dS^T Q asks for scale)
-Q / dO tiles arrive by direct global->LDS loads into a 4-stage ring, three blocks ahead; the per-row
+The (head, block) pairs of a key tile are walked block by block from the LAST block down, the query heads of
+the KV group being the inner index: workgroups of one XCD that work on key tiles of the same KV head then read
+the same rows of Q' and dO at about the same time whichever block their own tile's run starts at (under a causal
+mask the runs start at different blocks and all end at the last one), so those rows are fetched into the XCD's
+L2 once per round of tiles instead of once per workgroup.
+Q' / dO tiles arrive by direct global->LDS loads into a 4-stage ring, three blocks ahead; the per-row
 statistics (lse, Delta) are loaded three blocks ahead into registers, transformed once and written to LDS
 by every wavefront (identical values), so that no per-element VALU work is spent on them.
 
@@ -76,13 +81,17 @@ IN_V = 176                                           # v[176:191]
  I_LF16, I_STAT_L) = (176, 178, 180, 181, 182, 183, 184, 185, 186, 187, 188, 189, 190, 191)
 IN_SA, IN_SB = 32, 48                                # s[32:47], s[48:63]
 S_QPTR, S_DOPTR, S_LSEPTR, S_DLPTR = 32, 34, 36, 38
-S_QBS, S_QHS, S_DOBS, S_DOHS, S_STATHS, S_NBLK, S_NSTEPS = 40, 41, 42, 43, 44, 45, 46
+# The walk over the (query head, 32-row block) pairs of a key tile has the head as its inner index: S_NIN heads
+# per block, S_*IN bytes from one head to the next, S_*OUT bytes (signed, all three of one sign) from one block
+# to the next one visited.
+S_QIN, S_QOUT, S_DOIN, S_DOOUT, S_STOUT, S_NIN, S_NSTEPS, S_STIN = 40, 41, 42, 43, 44, 45, 46, 47
 S_VPTR, S_VRS16, S_LDS, S_DKPTR, S_DVPTR, S_WAVE, S_RS32, S_SCALE = 48, 50, 51, 52, 54, 56, 57, 58
 S_FLAGS, S_DKLP, S_DVLP = 59, 60, 62                # epilogue variant; bf16 copies of the dK / dV tile (if asked for)
 # scalar temporaries (clobbered)
 T_QPTR, T_QHEAD, T_DOPTR, T_DOHEAD = 64, 66, 68, 70
 T_LSEPTR, T_LSEHEAD, T_DLPTR, T_DLHEAD = 72, 74, 76, 78
 T_DBLK, T_DSTEP, T_ADV, T_WRAP, T_REM, T_M0, T_HIMASK, T_X, T_VPTR, T_INC, T_HINC = 80, 81, 82, 83, 84, 85, 86, 88, 90, 92, 93
+T_HI, T_OHI = 94, 95                                 # upper half of the outer increment: this step's, and when one is applied
 
 def ACC_K(db, nb): return 16 * (2 * db + nb)
 def ACC_V(db, nb): return 128 + 16 * (2 * db + nb)
@@ -99,27 +108,30 @@ BUDGET = int(os.environ.get("ST_GEN_DKV_BUDGET", 6 if D == 128 else 11))       #
 
 
 
-STREAMS = ((T_QPTR, T_QHEAD, S_QBS, S_QHS), (T_DOPTR, T_DOHEAD, S_DOBS, S_DOHS),
-           (T_LSEPTR, T_LSEHEAD, None, S_STATHS), (T_DLPTR, T_DLHEAD, None, S_STATHS))
+STREAMS = ((T_QPTR, T_QHEAD, S_QIN, S_QOUT), (T_DOPTR, T_DOHEAD, S_DOIN, S_DOOUT),
+           (T_LSEPTR, T_LSEHEAD, S_STIN, S_STOUT), (T_DLPTR, T_DLHEAD, S_STIN, S_STOUT))
 
 
 def advance_code():
-    """Branch-free move of the four global streams (Q, dO, lse, Delta) to the next block; they stay on the
-    last block once all of them have been requested.  Only these instructions (and the loop control behind
-    them) touch SCC between them, so they may be spread among non-scalar instructions."""
+    """Branch-free move of the four global streams (Q', dO, lse, Delta) to the next (head, block) pair; they stay
+    on the last one once all of them have been requested.  The inner increment (next head) is unsigned, the outer
+    one (next block, applied to the base of the current block when the heads wrap) is a signed 32-bit number whose
+    upper half T_OHI the prologue derives.  Only these instructions (and the loop control behind them) touch SCC
+    between them, so they may be spread among non-scalar instructions."""
     c = [f"s_add_u32 {sr(T_X)}, {sr(T_DSTEP)}, 1",
          f"s_cmp_lt_u32 {sr(T_X)}, {sr(S_NSTEPS)}",
          f"s_cselect_b32 {sr(T_DSTEP)}, {sr(T_X)}, {sr(T_DSTEP)}",
          f"s_cselect_b32 {sr(T_ADV)}, 1, 0",
          f"s_add_u32 {sr(T_X)}, {sr(T_DBLK)}, {sr(T_ADV)}",
-         f"s_cmp_eq_u32 {sr(T_X)}, {sr(S_NBLK)}",                       # only possible when advancing
+         f"s_cmp_eq_u32 {sr(T_X)}, {sr(S_NIN)}",                        # only possible when advancing
          f"s_cselect_b32 {sr(T_DBLK)}, 0, {sr(T_X)}",
-         f"s_cselect_b32 {sr(T_WRAP)}, -1, 0"]
+         f"s_cselect_b32 {sr(T_WRAP)}, -1, 0",
+         f"s_and_b32 {sr(T_HI)}, {sr(T_WRAP)}, {sr(T_OHI)}"]
     for ptr, head, bs, hs in STREAMS:
-        c.append(f"s_mul_i32 {sr(T_INC)}, {sr(T_ADV)}, {sr(bs)}" if bs is not None else f"s_lshl_b32 {sr(T_INC)}, {sr(T_ADV)}, 7")
+        c.append(f"s_mul_i32 {sr(T_INC)}, {sr(T_ADV)}, {sr(bs)}")
         c.append(f"s_and_b32 {sr(T_HINC)}, {sr(T_WRAP)}, {sr(hs)}")
         c += [f"s_add_u32 {sr(ptr)}, {sr(ptr)}, {sr(T_INC)}", f"s_addc_u32 {sr(ptr + 1)}, {sr(ptr + 1)}, 0",
-              f"s_add_u32 {sr(head)}, {sr(head)}, {sr(T_HINC)}", f"s_addc_u32 {sr(head + 1)}, {sr(head + 1)}, 0"]
+              f"s_add_u32 {sr(head)}, {sr(head)}, {sr(T_HINC)}", f"s_addc_u32 {sr(head + 1)}, {sr(head + 1)}, {sr(T_HI)}"]
     c.append(f"s_cmp_lg_u32 {sr(T_WRAP)}, 0")
     for ptr, head, bs, hs in STREAMS:
         c.append(f"s_cselect_b64 {sr(ptr, 2)}, {sr(head, 2)}, {sr(ptr, 2)}")
@@ -524,6 +536,7 @@ def generate():
     for t in (T_DBLK, T_DSTEP):
         e.raw(f"s_mov_b32 {sr(t)}, 0")
     e.raw(f"s_mov_b32 {sr(T_REM)}, {sr(S_NSTEPS)}")
+    e.raw(f"s_ashr_i32 {sr(T_OHI)}, {sr(S_QOUT)}, 31")     # sign extension of the outer increments
     e.raw(f"s_lshl_b32 {sr(T_M0)}, {sr(S_WAVE)}, 10")
     e.raw(f"s_add_u32 {sr(T_M0)}, {sr(T_M0)}, {sr(S_LDS)}")
     e.raw(f"s_mov_b32 {sr(T_HIMASK)}, 0")
@@ -622,7 +635,7 @@ def generate():
 def main():
     e = generate()
     clob = [f"v{i}" for i in range(256) if not (IN_V <= i < IN_V + 16)] + [f"a{i}" for i in range(256)]
-    clob += [f"s{i}" for i in range(64, 94)]
+    clob += [f"s{i}" for i in range(64, 96)]
     write_inc(sys.stdout, "gen_bwd_dkv_asm.py" + (" 64" if D == 64 else ""), "ST_DKV_FAST" + ("64" if D == 64 else ""), e,
               LDS_BYTES, clob)
 
