@@ -56,19 +56,26 @@ def mfma_ceiling(st, torch, data) -> dict:
     facts = st.st_device_facts()
     sink = torch.empty(facts["compute_units"] * 256, dtype=torch.float32, device="cuda")
     ones = torch.ones(1 << 20, dtype=torch.bfloat16, device="cuda")
-    out = {}
-    for name, ops in (("ones", ones), ("workload_q", data.reshape(-1))):
-        iters = 20000
-        st.st_mfma_probe(ops, 200, sink)
+
+    def rate(ops, mix):
+        per_iter = st.st_mfma_probe(ops, 1, sink, mix)               # flop of one iteration
+        iters = max(1, int(1.9e13 / per_iter))                        # about 10 ms
+        st.st_mfma_probe(ops, max(1, iters // 100), sink, mix)
         ms = []
         for _ in range(5):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            flop = st.st_mfma_probe(ops, iters, sink)
+            flop = st.st_mfma_probe(ops, iters, sink, mix)
             e1.record()
             torch.cuda.synchronize()
             ms.append(e0.elapsed_time(e1))
-        out[name] = round(flop / (sorted(ms)[2] * 1e-3) / 1e12, 1)
+        return round(flop / (sorted(ms)[2] * 1e-3) / 1e12, 1)
+
+    out = {"ones": rate(ones, 0), "workload_q": rate(data.reshape(-1), 0)}
+    # the same loop with side instructions beside the MFMAs, on the workload's data: the price of each kind of
+    # instruction, and the ceiling of each hand-scheduled loop's instruction mix (head size 128)
+    out["workload_q_with_side_instructions"] = {
+        st.st_mfma_probe_mix_name(m): rate(data.reshape(-1), m) for m in range(1, st.st_mfma_probe_mixes() + 1)}
     return out
 
 
@@ -321,6 +328,15 @@ def main() -> int:
     # nominal peak from the device the run is on: CUs x 4096 bf16 flop per clock and CU x maximum shader clock
     peak_nominal = facts["compute_units"] * 4096 * facts["max_clock_mhz"] * 1e6 / 1e12 if bf16 else None
     ceiling = mfma_ceiling(st, torch, q) if bf16 else None
+    if ceiling and w.D == 128 and mode == st.ST_RING_FUSED:
+        # executed MFMA work of each hand-scheduled loop (the dQ loop recomputes S and dP: 6 D per pair for the 2 D it
+        # is credited with) against what its instruction mix alone reaches on the workload's data
+        mixes = ceiling["workload_q_with_side_instructions"]
+        for name, mix, executed_per_credited in (("fwd_bf16", "fwd", 1), ("bwd_dkv_bf16", "dkv", 1), ("bwd_dq_bf16", "dq", 3)):
+            if name in per_kernel and "algorithmic_tflops" in per_kernel[name]:
+                ex = per_kernel[name]["algorithmic_tflops"] * executed_per_credited
+                per_kernel[name]["executed_tflops"] = round(ex, 1)
+                per_kernel[name]["frac_of_instruction_mix_ceiling"] = round(ex / mixes[mix], 3)
     roofline = None
     if dom is not None:
         launches, total_ms = kernels[dom]

@@ -312,17 +312,25 @@ typedef struct {
 } st_device_report;
 st_status st_device_facts(st_device_report* out);
 
-/* ---- MFMA-only loop for benchmarks (not part of the method) ----
+/* ---- MFMA loops for benchmarks (not part of the method) ----
  * One workgroup of four wavefronts per compute unit; every wavefront loads 16 operand fragments (16 bytes per
- * lane each) from `operands` and then issues iters x 32 v_mfma_f32_32x32x16_bf16 on them and nothing else.
+ * lane each) from `operands` and then runs `iters` iterations of a loop of v_mfma_f32_32x32x16_bf16 on them.
  * Timed by the caller (events on the stream), it gives the rate the matrix units sustain on THAT data, which is
  * the ceiling to compare an attention kernel with: the chip runs at its power limit, and the limit depends on
- * the operand values.
+ * the operand values and on what is issued beside the MFMAs.
+ *   mix       0: nothing but MFMAs (32 per iteration).  1 .. st_mfma_probe_mixes(): side instructions with
+ *             independent operands are spread between the MFMAs (st_mfma_probe_mix_name: "valu2" two v_mul_f32
+ *             per MFMA, "exp1" one v_exp_f32, "pack2" two v_cvt_pk_bf16_f32, "lds1" one 16-byte LDS read,
+ *             "ldstr1" one transposing 8-byte LDS read; "fwd", "dq", "dkv": the instruction counts per key block of
+ *             the forward, dQ and dK/dV loops at head size 128, without their dependencies, barriers and global
+ *             loads - what such a mix reaches bounds that loop on the same data)
  *   operands  device, 16-byte aligned, operand_bytes >= 65536 bytes of bf16 values (read with wrap-around)
  *   sink      device, sink_floats >= 256 * compute units floats (overwritten; keeps the loop alive)
- *   flop      host, nullable: floating point operations the launch executes (2 per multiply-add) */
-st_status st_mfma_probe(const void* operands, int64_t operand_bytes, int32_t iters, float* sink,
+ *   flop      host, nullable: floating point operations of the MFMAs the launch executes (2 per multiply-add) */
+st_status st_mfma_probe(const void* operands, int64_t operand_bytes, int32_t mix, int32_t iters, float* sink,
                         int64_t sink_floats, double* flop, void* hip_stream);
+int32_t     st_mfma_probe_mixes(void);
+const char* st_mfma_probe_mix_name(int32_t mix);   /* "" for a mix out of range */
 
 /* ---- misc ---- */
 const char* st_status_str(st_status s);

@@ -99,7 +99,9 @@ def _load() -> C.CDLL:
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
                                        C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, C.c_size_t, vp]),
         "st_device_facts": (C.c_int, [C.POINTER(st_device_report)]),
-        "st_mfma_probe": (C.c_int, [vp, C.c_int64, C.c_int32, f32p, C.c_int64, C.POINTER(C.c_double), vp]),
+        "st_mfma_probe": (C.c_int, [vp, C.c_int64, C.c_int32, C.c_int32, f32p, C.c_int64, C.POINTER(C.c_double), vp]),
+        "st_mfma_probe_mixes": (C.c_int32, []),
+        "st_mfma_probe_mix_name": (C.c_char_p, [C.c_int32]),
         "st_profile_begin": (C.c_int, []),
         "st_profile_end": (C.c_int, [C.POINTER(st_profile_entry), C.c_int32, C.POINTER(C.c_int32)]),
         "st_status_str": (C.c_char_p, [C.c_int]),
@@ -114,7 +116,7 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["st_attn_block_fwd", "st_attn_merge", "st_attn_combine", "st_attn_delta", "st_attn_block_bwd", "st_attn_block_bwd_workspace_bytes", "st_cast_from_f32",
-           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_noalloc", "st_ring_bwd_noalloc_max_bytes", "st_ring_bwd_last", "st_device_facts", "st_mfma_probe", "st_profile_begin",
+           "st_visit_order", "st_team_visit_order", "st_schedule_report", "st_ring_workspace_bytes", "st_ring_fwd", "st_ring_bwd", "st_ring_bwd_noalloc", "st_ring_bwd_noalloc_max_bytes", "st_ring_bwd_last", "st_device_facts", "st_mfma_probe", "st_mfma_probe_mixes", "st_mfma_probe_mix_name", "st_profile_begin",
            "st_profile_end", "st_status_str",
            "st_last_error", "st_version"]
 
@@ -202,14 +204,23 @@ def st_device_facts() -> dict:
             "memory_bus_bits": int(r.memory_bus_bits), "hbm_bytes": int(r.hbm_bytes)}
 
 
-def st_mfma_probe(operands: torch.Tensor, iters: int, sink: torch.Tensor, stream=None) -> float:
-    """Enqueues the MFMA-only loop on `operands` (any contiguous tensor, read as bf16 bits); returns the flop it executes."""
+def st_mfma_probe(operands: torch.Tensor, iters: int, sink: torch.Tensor, mix: int = 0, stream=None) -> float:
+    """Enqueues the MFMA loop `mix` (0: MFMAs only) on `operands` (any contiguous tensor, read as bf16 bits);
+    returns the flop its MFMAs execute."""
     if not operands.is_contiguous() or sink.dtype != torch.float32 or not sink.is_contiguous():
         raise ValueError("operands must be contiguous, sink contiguous fp32")
     flop = C.c_double(0.0)
-    _check(_lib.st_mfma_probe(_ptr(operands), operands.numel() * operands.element_size(), int(iters), _ptr(sink),
+    _check(_lib.st_mfma_probe(_ptr(operands), operands.numel() * operands.element_size(), int(mix), int(iters), _ptr(sink),
                               sink.numel(), C.byref(flop), _stream(stream)), "st_mfma_probe")
     return float(flop.value)
+
+
+def st_mfma_probe_mixes() -> int:
+    return int(_lib.st_mfma_probe_mixes())
+
+
+def st_mfma_probe_mix_name(mix: int) -> str:
+    return _lib.st_mfma_probe_mix_name(int(mix)).decode()
 
 
 def st_profile_begin() -> None:

@@ -20,7 +20,8 @@ SOURCES = ["st_api.cpp", "st_runtime.cpp", "st_f32.hip", "st_elementwise.hip", "
 # assembly main loops written out by generator scripts before compiling: (script, output)
 GENERATED = [("gen_bwd_dkv_asm.py", "st_bwd_dkv_asm.inc"), ("gen_bwd_dq_asm.py", "st_bwd_dq_asm.inc"),
              ("gen_fwd_asm.py", "st_fwd_asm.inc"), ("gen_fwd_asm.py 64", "st_fwd64_asm.inc"),
-             ("gen_bwd_dq_asm.py 64", "st_bwd_dq64_asm.inc"), ("gen_bwd_dkv_asm.py 64", "st_bwd_dkv64_asm.inc")]
+             ("gen_bwd_dq_asm.py 64", "st_bwd_dq64_asm.inc"), ("gen_bwd_dkv_asm.py 64", "st_bwd_dkv64_asm.inc"),
+             ("gen_probe_asm.py", "st_probe_asm.inc")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms (v_pk_add_f32, v_pk_mul_f32, v_pk_fma_f32) are switched off for device code on purpose:

@@ -241,18 +241,22 @@ st_status st_profile_end(st_profile_entry* out, int32_t max_entries, int32_t* n_
   return status;
 }
 
-st_status st_mfma_probe(const void* operands, int64_t operand_bytes, int32_t iters, float* sink, int64_t sink_floats,
-                        double* flop, void* hip_stream) {
+st_status st_mfma_probe(const void* operands, int64_t operand_bytes, int32_t mix, int32_t iters, float* sink,
+                        int64_t sink_floats, double* flop, void* hip_stream) {
   if (operands == nullptr || sink == nullptr) return fail(ST_ERR_INVALID_ARG, "null pointer");
   if (reinterpret_cast<uintptr_t>(operands) % 16) return fail(ST_ERR_ALIGNMENT, "operands: not 16-byte aligned");
   if (operand_bytes < 65536) return fail(ST_ERR_INVALID_ARG, "operands: at least 65536 bytes are needed");
   if (iters < 1 || iters > (1 << 24)) return fail(ST_ERR_INVALID_ARG, "iters must be in 1 .. 2^24");
+  if (mix < 0 || mix > st::mfma_probe_mixes()) return fail(ST_ERR_INVALID_ARG, "mix must be in 0 .. %d", st::mfma_probe_mixes());
   const int blocks = st::mfma_probe_blocks();
   if (sink_floats < (int64_t)blocks * 256) return fail(ST_ERR_INVALID_ARG, "sink: %lld floats are needed", (long long)blocks * 256);
-  ST_HIP(st::launch_mfma_probe(operands, operand_bytes, iters, sink, blocks, (hipStream_t)hip_stream), "st_mfma_probe launch");
-  if (flop) *flop = st::mfma_probe_flop(blocks, iters);
+  ST_HIP(st::launch_mfma_probe(operands, operand_bytes, mix, iters, sink, blocks, (hipStream_t)hip_stream), "st_mfma_probe launch");
+  if (flop) *flop = st::mfma_probe_flop(blocks, mix, iters);
   return ST_OK;
 }
+
+int32_t st_mfma_probe_mixes(void) { return st::mfma_probe_mixes(); }
+const char* st_mfma_probe_mix_name(int32_t mix) { return st::mfma_probe_mix_name(mix); }
 
 st_status st_device_facts(st_device_report* out) {
   if (out == nullptr) return fail(ST_ERR_INVALID_ARG, "null output");

@@ -214,7 +214,10 @@ hipError_t launch_fill_state(float* o, float* lse, int64_t n_o, int64_t n_lse, h
 hipError_t launch_zero(void* dst, int64_t bytes, hipStream_t s);   // bytes % 4 == 0, dst 4-byte aligned
 // benchmark aid: MFMA-only loop, one workgroup per compute unit (see st_probe.hip)
 int mfma_probe_blocks();
-double mfma_probe_flop(int blocks, int32_t iters);
-hipError_t launch_mfma_probe(const void* operands, int64_t operand_bytes, int32_t iters, float* sink, int blocks, hipStream_t s);
+int mfma_probe_mixes();                              // side-instruction mixes 1 .. mfma_probe_mixes(); 0 = MFMAs only
+const char* mfma_probe_mix_name(int mix);
+double mfma_probe_flop(int blocks, int mix, int32_t iters);
+hipError_t launch_mfma_probe(const void* operands, int64_t operand_bytes, int mix, int32_t iters, float* sink, int blocks,
+                             hipStream_t s);
 
 }  // namespace st
