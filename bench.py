@@ -328,7 +328,7 @@ def main() -> int:
     # nominal peak from the device the run is on: CUs x 4096 bf16 flop per clock and CU x maximum shader clock
     peak_nominal = facts["compute_units"] * 4096 * facts["max_clock_mhz"] * 1e6 / 1e12 if bf16 else None
     ceiling = mfma_ceiling(st, torch, q) if bf16 else None
-    if ceiling and w.D == 128 and mode == st.ST_RING_FUSED:
+    if ceiling and w.D in (64, 128) and mode == st.ST_RING_FUSED:
         # executed MFMA work of each hand-scheduled loop (the dQ loop recomputes S and dP: 6 D per pair for the 2 D it
         # is credited with) against what its instruction mix alone reaches on the workload's data
         mixes = ceiling["workload_q_with_side_instructions"]
@@ -336,7 +336,7 @@ def main() -> int:
             if name in per_kernel and "algorithmic_tflops" in per_kernel[name]:
                 ex = per_kernel[name]["algorithmic_tflops"] * executed_per_credited
                 per_kernel[name]["executed_tflops"] = round(ex, 1)
-                per_kernel[name]["frac_of_instruction_mix_ceiling"] = round(ex / mixes[mix], 3)
+                per_kernel[name]["frac_of_instruction_mix_ceiling"] = round(ex / mixes[mix + ("64" if w.D == 64 else "")], 3)
     roofline = None
     if dom is not None:
         launches, total_ms = kernels[dom]

@@ -321,9 +321,10 @@ st_status st_device_facts(st_device_report* out);
  *   mix       0: nothing but MFMAs (32 per iteration).  1 .. st_mfma_probe_mixes(): side instructions with
  *             independent operands are spread between the MFMAs (st_mfma_probe_mix_name: "valu2" two v_mul_f32
  *             per MFMA, "exp1" one v_exp_f32, "pack2" two v_cvt_pk_bf16_f32, "lds1" one 16-byte LDS read,
- *             "ldstr1" one transposing 8-byte LDS read; "fwd", "dq", "dkv": the instruction counts per key block of
- *             the forward, dQ and dK/dV loops at head size 128, without their dependencies, barriers and global
- *             loads - what such a mix reaches bounds that loop on the same data)
+ *             "ldstr1" one transposing 8-byte LDS read; "fwd", "dq", "dkv" and "fwd64", "dq64", "dkv64": the
+ *             instruction counts per key block of the forward, dQ and dK/dV loops at head sizes 128 and 64,
+ *             without their dependencies, barriers and global loads - what such a mix reaches bounds that loop
+ *             on the same data)
  *   operands  device, 16-byte aligned, operand_bytes >= 65536 bytes of bf16 values (read with wrap-around)
  *   sink      device, sink_floats >= 256 * compute units floats (overwritten; keeps the loop alive)
  *   flop      host, nullable: floating point operations of the MFMAs the launch executes (2 per multiply-add) */
