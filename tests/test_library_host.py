@@ -169,3 +169,24 @@ def test_ring_bwd_last_validation_fails_before_any_launch():
     assert call(lk=odd, lv=both) == 3                          # misaligned copy
     assert call(dtype=0, lk=both, lv=both) == 2                # bf16 copies of an fp32 problem
     assert call(flags=1, lk=both, lv=both, ws=0) == 5          # arguments fine: stops at the missing workspace
+
+
+def test_mfma_probe_mixes_and_validation():
+    """The benchmark probe: its mixes have names, and bad arguments fail before any launch."""
+    n = api.st_mfma_probe_mixes()
+    names = [api.st_mfma_probe_mix_name(m) for m in range(n + 1)]
+    assert names[0] == "none" and len(set(names)) == n + 1 and all(names)
+    assert {"fwd", "dq", "dkv", "fwd64", "dq64", "dkv64"} <= set(names)
+    assert api.st_mfma_probe_mix_name(n + 1) == "" and api.st_mfma_probe_mix_name(-1) == ""
+    flop = C.c_double(-1.0)
+
+    def call(ops=0x10000, nbytes=1 << 20, mix=0, iters=10, sink=0x20000, nsink=1 << 20):
+        return api._lib.st_mfma_probe(C.c_void_p(ops), nbytes, mix, iters, C.cast(C.c_void_p(sink), C.POINTER(C.c_float)),
+                                      nsink, C.byref(flop), None)
+
+    assert call(ops=0) == 1 and call(sink=0) == 1
+    assert call(ops=0x10008) == 3                       # not 16-byte aligned
+    assert call(nbytes=4096) == 1 and call(iters=0) == 1 and call(iters=(1 << 24) + 1) == 1
+    assert call(mix=-1) == 1 and call(mix=n + 1) == 1
+    assert call(nsink=16) == 1                          # the sink holds one float per thread of the launch
+    assert flop.value == -1.0
