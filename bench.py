@@ -324,6 +324,10 @@ def main() -> int:
         if name in algo and mode == st.ST_RING_FUSED:
             per_kernel[name]["algorithmic_tflops"] = round(algo[name] / (avg * 1e-3) / 1e12, 1)
     dom = max((n for n in kernels if n in algo), key=lambda n: kernels[n][1], default=None)
+    # HIP-event time of the forward and of the backward kernels of a step (the sums of the per-kernel times above)
+    fwd_names = {"fwd_bf16", "fwd_edge", "fwd_f32", "combine", "merge"}
+    ms_fwd = sum(t for n, (_, t) in kernels.items() if n in fwd_names) / prof_steps
+    ms_bwd = sum(t for n, (_, t) in kernels.items() if n not in fwd_names) / prof_steps
     facts = st.st_device_facts()
     # nominal peak from the device the run is on: CUs x 4096 bf16 flop per clock and CU x maximum shader clock
     peak_nominal = facts["compute_units"] * 4096 * facts["max_clock_mhz"] * 1e6 / 1e12 if bf16 else None
@@ -355,6 +359,7 @@ def main() -> int:
         "metric": "fwd+bwd attention TFLOP/s on 1 MI355X + % of bf16 MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "ms_median": round(ms_median, 4), "ms_min": round(ms_min, 4),
+        "ms_kernels_by_pass": {"fwd": round(ms_fwd, 4), "bwd": round(ms_bwd, 4)},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "Sq": w.Sq, "Sk": w.Sk,
