@@ -423,6 +423,7 @@ def cpu_baseline(w, inp, met=None) -> dict:
             pairs += len(rows) * w.Sk * len(met)
     secs = time.perf_counter() - t0
     flop = (4 + (10 if w.backward else 0)) * w.D * pairs * w.B
+    fraction = pairs / max(si.visible_pairs(w, met) * w.Hq, 1)          # of the workload's visible (query, key, head) triples
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -431,7 +432,8 @@ def cpu_baseline(w, inp, met=None) -> dict:
     return {"value": round(flop / secs / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"{rows_per_head} seeded query rows of each of {len(heads)} heads (KV head 0) against the "
                       f"{w.Sk * len(met)} keys it meets, fwd{'+bwd' if w.backward else ''}, numpy fp64",
-            "seconds": round(secs, 2)}
+            "seconds": round(secs, 2), "fraction_of_workload": float(f"{fraction:.3e}"),
+            "extrapolated_full_seconds": round(secs / fraction, 0)}
 
 
 if __name__ == "__main__":
