@@ -79,9 +79,37 @@ def mfma_ceiling(st, torch, data) -> dict:
     return out
 
 
+def queue_filler(st, torch):
+    """Keeps the GPU busy for a few milliseconds (the MFMA probe on a small buffer) so that the short launches
+    enqueued behind it are all in the queue before the first of them starts: their HIP-event intervals then
+    measure the kernels back to back and not how fast the host can launch."""
+    facts = st.st_device_facts()
+    sink = torch.empty(facts["compute_units"] * 256, dtype=torch.float32, device="cuda")
+    ones = torch.ones(1 << 16, dtype=torch.bfloat16, device="cuda")
+    return lambda: st.st_mfma_probe(ones, 8000, sink)
+
+
+def batch_time(torch, fill_queue, launch, n: int = 16, batches: int = 5) -> float:
+    """Milliseconds per launch of a short kernel: n launches between two HIP events on the launch stream, enqueued
+    behind a filler so that they run back to back; median of `batches` such batches."""
+    per_launch = []
+    for _ in range(batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        fill_queue()
+        e0.record()
+        for i in range(n):
+            launch(i)
+        e1.record()
+        torch.cuda.synchronize()
+        per_launch.append(e0.elapsed_time(e1) / n)
+    return sorted(per_launch)[batches // 2]
+
+
 def merge_pass(st, torch, w) -> dict:
     """HBM rate of the log-sum-exp merge (st_attn_merge) at this workload's state size.  Four buffer sets are
     rotated so that no operand of a launch is left in the 256 MB last-level cache by the launch before."""
+    fill_queue = queue_filler(st, torch)
     sets = []
     for _ in range(4):
         o_a = torch.randn((w.B, w.Sq, w.Hq, w.D), device="cuda")
@@ -91,14 +119,7 @@ def merge_pass(st, torch, w) -> dict:
         sets.append((o_a, l_a, o_p, l_p))
     for i in range(4):
         st.st_attn_merge(*sets[i])
-    n = 16
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
-    ev[0].record()
-    for i in range(n):
-        st.st_attn_merge(*sets[i % 4])
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2]
+    ms = batch_time(torch, fill_queue, lambda i: st.st_attn_merge(*sets[i % 4]))
     rows = w.B * w.Hq * w.Sq
     nbytes = rows * (12 * w.D + 12)               # two states read, one written: D + 1 floats each
     gbs = nbytes / (ms * 1e-3) / 1e9
@@ -117,14 +138,9 @@ def combine_pass(st, torch, states_o, states_l, n_own, w) -> dict:
     low = torch.empty((w.B, n_own, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
     for a in range(Ct):
         st.st_attn_combine(states_o, states_l, a * n_own, n_own, st.ST_BF16, o_out=o, lse_out=l, o_out_lowp=low)
-    n = 16
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
-    ev[0].record()
-    for i in range(n):
-        st.st_attn_combine(states_o, states_l, (i % Ct) * n_own, n_own, st.ST_BF16, o_out=o, lse_out=l, o_out_lowp=low)
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(n))[n // 2]
+    ms = batch_time(torch, queue_filler(st, torch),
+                    lambda i: st.st_attn_combine(states_o, states_l, (i % Ct) * n_own, n_own, st.ST_BF16, o_out=o, lse_out=l,
+                                                 o_out_lowp=low))
     rows = w.B * w.Hq * n_own
     nbytes = rows * (Ct * (4 * w.D + 4) + 4 * w.D + 4 + 2 * w.D)
     gbs = nbytes / (ms * 1e-3) / 1e9
