@@ -19,57 +19,54 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// ---- merge: thread = one float4 of one (b, i, h) row -----------------------------------------
-// A row occupies a power-of-two group of lanes (lanes beyond vec_per_row idle), so a row never
-// straddles a wavefront: every lane of the row has read lse_acc before lane 0 overwrites it.
+// ---- merge: thread = up to U float4 of one (b, i, h) row ---------------------------------------
+// A row occupies a power-of-two group of lanes; lane `sub` of the group takes the vectors sub, sub + lanes, ...
+// of the row, so consecutive lanes read consecutive 16-byte pieces (whole 128-byte lines once the group has
+// eight lanes), the row's two lse are read once per U vectors and its weights are computed once.
+// The group never straddles a wavefront: every lane of the row has read lse_acc before lane 0 overwrites it.
 // Weights: w_acc = exp(lse_acc - lse'), w_part = exp(lse_part - lse'), lse' = max + log(sum).
 // A side with lse = -inf gets weight 0 without ever forming (-inf) - (-inf), and its O is not read into the sum.
-constexpr int kMergeUnroll = 4;   // vectors per thread: all loads of a thread are in flight before its first store
-
-template <bool kLowp>
+// U = vectors per thread (1, 2 or 4): all loads of a thread are in flight before its first store.
+template <bool kLowp, int U>
 __global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, float* __restrict__ lse_acc,
                                                     const float* __restrict__ o_part,
                                                     const float* __restrict__ lse_part, int64_t n_rows,
                                                     int32_t Sq, int32_t Hq, int32_t vec_per_row,
                                                     int32_t lane_shift, uint2* __restrict__ o_lowp) {
-  int64_t v[kMergeUnroll], sidx[kMergeUnroll];
-  bool live[kMergeUnroll], first[kMergeUnroll];
-  float la[kMergeUnroll], lp[kMergeUnroll];
-  float4 a[kMergeUnroll], p[kMergeUnroll];
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = tid >> lane_shift;               // (b * Sq + i) * Hq + h
+  const int32_t sub = (int32_t)(tid & ((1 << lane_shift) - 1));
+  if (row >= n_rows) return;
+  const int32_t h = (int32_t)(row % Hq);
+  const int64_t bi = row / Hq;
+  const int64_t sidx = ((bi / Sq) * Hq + h) * Sq + (bi % Sq);
+  const float la = lse_acc[sidx], lp = lse_part[sidx];
+  int64_t v[U];
+  bool live[U];
+  float4 a[U], p[U];
 #pragma unroll
-  for (int u = 0; u < kMergeUnroll; ++u) {
-    const int64_t tid = ((int64_t)blockIdx.x * kMergeUnroll + u) * 256 + threadIdx.x;
-    const int64_t row = tid >> lane_shift;             // (b * Sq + i) * Hq + h
-    const int32_t sub = (int32_t)(tid & ((1 << lane_shift) - 1));
-    live[u] = row < n_rows && sub < vec_per_row;
-    first[u] = sub == 0;
-    const int64_t rr = live[u] ? row : 0;
-    v[u] = rr * vec_per_row + (live[u] ? sub : 0);
-    const int32_t h = (int32_t)(rr % Hq);
-    const int64_t bi = rr / Hq;
-    sidx[u] = ((bi / Sq) * Hq + h) * Sq + (bi % Sq);
-    la[u] = lse_acc[sidx[u]];
-    lp[u] = lse_part[sidx[u]];
+  for (int u = 0; u < U; ++u) {
+    const int32_t vi = sub + (u << lane_shift);
+    live[u] = vi < vec_per_row;
+    v[u] = row * vec_per_row + (live[u] ? vi : 0);     // a slot beyond the row reads its first vector and stores nothing
     a[u] = reinterpret_cast<const float4*>(o_acc)[v[u]];
-    {
-      typedef float f32x4_t __attribute__((ext_vector_type(4)));
-      const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(o_part) + v[u]);   // read once
-      p[u] = make_float4(t.x, t.y, t.z, t.w);
-    }
+    typedef float f32x4_t __attribute__((ext_vector_type(4)));
+    const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(o_part) + v[u]);   // read once
+    p[u] = make_float4(t.x, t.y, t.z, t.w);
+  }
+  const float m = fmaxf(la, lp);
+  float wa = 0.f, wp = 0.f, lnew = -INFINITY;
+  if (m != -INFINITY) {
+    const float ea = expf(la - m), ep = expf(lp - m);  // exp(-inf) = 0 for an empty side
+    const float sum = ea + ep;
+    lnew = m + logf(sum);
+    const float inv = 1.f / sum;
+    wa = ea * inv;
+    wp = ep * inv;
   }
 #pragma unroll
-  for (int u = 0; u < kMergeUnroll; ++u) {
+  for (int u = 0; u < U; ++u) {
     if (!live[u]) continue;
-    const float m = fmaxf(la[u], lp[u]);
-    float wa = 0.f, wp = 0.f, lnew = -INFINITY;
-    if (m != -INFINITY) {
-      const float ea = expf(la[u] - m), ep = expf(lp[u] - m);  // exp(-inf) = 0 for an empty side
-      const float sum = ea + ep;
-      lnew = m + logf(sum);
-      const float inv = 1.f / sum;
-      wa = ea * inv;
-      wp = ep * inv;
-    }
     // a side whose weight is exactly 0 (an empty state) is left out, so that a non-finite value in its O
     // (never written, or stale) cannot turn the result into NaN; the combine pass does the same
     const float4 za = wa != 0.f ? a[u] : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -81,8 +78,8 @@ __global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, f
     r.w = wa * za.w + wp * zp.w;
     reinterpret_cast<float4*>(o_acc)[v[u]] = r;
     if (kLowp) o_lowp[v[u]] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
-    if (first[u]) lse_acc[sidx[u]] = lnew;
   }
+  if (sub == 0) lse_acc[sidx] = lnew;
 }
 
 // ---- combine: n partial states of the same rows -> one state, keeping a run of rows -----------
@@ -91,8 +88,9 @@ __global__ __launch_bounds__(256) void merge_kernel(float* __restrict__ o_acc, f
 // weighs 0 and (-inf) - (-inf) is never formed; a row empty in every state gives O = 0, lse = -inf.
 // The O loads of kCombineUnroll states are in flight together.
 constexpr int kCombineUnroll = 4;
+constexpr int kCombineFew = 2 * kCombineUnroll;
 
-template <bool kLowp>
+template <bool kLowp, bool kFew>
 __global__ __launch_bounds__(256) void combine_kernel(const CombineArgs a, int32_t vec_per_row, int32_t lane_shift) {
   const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = tid >> lane_shift;               // (b * Sq_out + i) * Hq + h
@@ -106,35 +104,70 @@ __global__ __launch_bounds__(256) void combine_kernel(const CombineArgs a, int32
   const int64_t l_in = (b * a.Hq + h) * a.Sq_in + a.row0 + i;
   const int64_t v_in = ((b * a.Sq_in + a.row0 + i) * a.Hq + h) * vec_per_row + sub;
 
-  float m = -INFINITY;
-  for (int x = 0; x < a.n; ++x) m = fmaxf(m, a.lse[x][l_in]);
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  auto load_o = [&](int x) {
+    const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(a.o[x]) + v_in);   // read once
+    return make_float4(t.x, t.y, t.z, t.w);
+  };
+  // a weight of exactly 0 must not turn a non-finite value of an empty state into NaN
+  auto add = [](float4& r, float w, const float4& p) {
+    if (w != 0.f) {
+      r.x = fmaf(w, p.x, r.x);
+      r.y = fmaf(w, p.y, r.y);
+      r.z = fmaf(w, p.z, r.z);
+      r.w = fmaf(w, p.w, r.w);
+    }
+  };
   float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
   float lnew = -INFINITY;
-  if (m != -INFINITY) {
-    float sum = 0.f;
-    for (int x = 0; x < a.n; ++x) sum += expf(a.lse[x][l_in] - m);
-    lnew = m + logf(sum);
-    const float inv = 1.f / sum;
-    for (int x0 = 0; x0 < a.n; x0 += kCombineUnroll) {
-      float4 p[kCombineUnroll];
-      float w[kCombineUnroll];
+  if (kFew) {
+    // up to kCombineFew states (a team): every lse is read once and kept, and the first O loads do not wait for them
+    float l[kCombineFew];
+    float4 p[kCombineUnroll];
 #pragma unroll
-      for (int u = 0; u < kCombineUnroll; ++u) {
-        const int x = x0 + u < a.n ? x0 + u : a.n - 1;
-        typedef float f32x4_t __attribute__((ext_vector_type(4)));
-        const f32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(a.o[x]) + v_in);   // read once
-        p[u] = make_float4(t.x, t.y, t.z, t.w);
-        w[u] = x0 + u < a.n ? expf(a.lse[x][l_in] - m) * inv : 0.f;
+    for (int x = 0; x < kCombineFew; ++x) l[x] = x < a.n ? a.lse[x][l_in] : -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kCombineUnroll; ++u) p[u] = load_o(u < a.n ? u : a.n - 1);
+    float m = -INFINITY;
+#pragma unroll
+    for (int x = 0; x < kCombineFew; ++x) m = fmaxf(m, l[x]);
+    if (m != -INFINITY) {
+      float sum = 0.f;
+#pragma unroll
+      for (int x = 0; x < kCombineFew; ++x) {
+        l[x] = expf(l[x] - m);                           // exp(-inf) = 0 for an empty state and for x >= n
+        sum += l[x];
       }
+      lnew = m + logf(sum);
+      const float inv = 1.f / sum;
 #pragma unroll
-      for (int u = 0; u < kCombineUnroll; ++u) {
-        // a weight of exactly 0 must not turn a non-finite value of an empty state into NaN
-        if (w[u] != 0.f) {
-          r.x = fmaf(w[u], p[u].x, r.x);
-          r.y = fmaf(w[u], p[u].y, r.y);
-          r.z = fmaf(w[u], p[u].z, r.z);
-          r.w = fmaf(w[u], p[u].w, r.w);
+      for (int u = 0; u < kCombineUnroll; ++u) add(r, u < a.n ? l[u] * inv : 0.f, p[u]);
+      if (a.n > kCombineUnroll) {
+#pragma unroll
+        for (int u = 0; u < kCombineUnroll; ++u) p[u] = load_o(kCombineUnroll + u < a.n ? kCombineUnroll + u : a.n - 1);
+#pragma unroll
+        for (int u = 0; u < kCombineUnroll; ++u) add(r, kCombineUnroll + u < a.n ? l[kCombineUnroll + u] * inv : 0.f, p[u]);
+      }
+    }
+  } else {
+    float m = -INFINITY;
+    for (int x = 0; x < a.n; ++x) m = fmaxf(m, a.lse[x][l_in]);
+    if (m != -INFINITY) {
+      float sum = 0.f;
+      for (int x = 0; x < a.n; ++x) sum += expf(a.lse[x][l_in] - m);
+      lnew = m + logf(sum);
+      const float inv = 1.f / sum;
+      for (int x0 = 0; x0 < a.n; x0 += kCombineUnroll) {
+        float4 p[kCombineUnroll];
+        float w[kCombineUnroll];
+#pragma unroll
+        for (int u = 0; u < kCombineUnroll; ++u) {
+          const int x = x0 + u < a.n ? x0 + u : a.n - 1;
+          p[u] = load_o(x);
+          w[u] = x0 + u < a.n ? expf(a.lse[x][l_in] - m) * inv : 0.f;
         }
+#pragma unroll
+        for (int u = 0; u < kCombineUnroll; ++u) add(r, w[u], p[u]);
       }
     }
   }
@@ -251,17 +284,29 @@ hipError_t launch_merge(float* o_acc, float* lse_acc, const float* o_part, const
   const int64_t n_rows = (int64_t)B * Sq * Hq;
   const int64_t n_vec = n_rows * (D / 4);
   if (n_vec == 0) return hipSuccess;
+  // lanes per row and vectors per lane: eight lanes where the row has that many vectors (a group then reads whole
+  // 128-byte lines), up to four vectors each, more lanes for the longest rows (D <= 256: at most 16)
+  const int vec = D / 4;
   int lane_shift = 0;
-  while ((1 << lane_shift) < D / 4) ++lane_shift;      // D <= 256 -> at most 64 lanes per row
-  const unsigned blocks = blocks_for(((n_rows << lane_shift) + kMergeUnroll - 1) / kMergeUnroll);
+  while ((1 << lane_shift) < 8 && (1 << lane_shift) < vec) ++lane_shift;
+  while ((4 << lane_shift) < vec) ++lane_shift;
+  const int per_lane = (vec + (1 << lane_shift) - 1) >> lane_shift;      // 1 .. 4
+  const unsigned blocks = blocks_for(n_rows << lane_shift);
+  const bool lowp = o_lowp != nullptr && lowp_dtype == ST_BF16;
   ProfScope prof("merge", s);
-  if (o_lowp != nullptr && lowp_dtype == ST_BF16) {
-    hipLaunchKernelGGL(merge_kernel<true>, dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part,
-                       n_rows, Sq, Hq, D / 4, lane_shift, (uint2*)o_lowp);
+#define ST_LAUNCH_MERGE(LOWP, U)                                                                                    \
+  hipLaunchKernelGGL((merge_kernel<LOWP, U>), dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part, n_rows, \
+                     Sq, Hq, vec, lane_shift, (uint2*)(LOWP ? o_lowp : nullptr))
+  if (lowp) {
+    if (per_lane == 1) ST_LAUNCH_MERGE(true, 1);
+    else if (per_lane == 2) ST_LAUNCH_MERGE(true, 2);
+    else ST_LAUNCH_MERGE(true, 4);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(merge_kernel<false>, dim3(blocks), dim3(256), 0, s, o_acc, lse_acc, o_part, lse_part,
-                     n_rows, Sq, Hq, D / 4, lane_shift, (uint2*)nullptr);
+  if (per_lane == 1) ST_LAUNCH_MERGE(false, 1);
+  else if (per_lane == 2) ST_LAUNCH_MERGE(false, 2);
+  else ST_LAUNCH_MERGE(false, 4);
+#undef ST_LAUNCH_MERGE
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && o_lowp != nullptr) {
     hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n_vec)), dim3(256), 0, s, (const float4*)o_acc,
@@ -280,10 +325,12 @@ hipError_t launch_combine(const CombineArgs& a, int lowp_dtype, hipStream_t s) {
   const unsigned blocks = blocks_for(n_rows << lane_shift);
   ProfScope prof("combine", s);
   if (a.o_lowp != nullptr && lowp_dtype == ST_BF16) {
-    hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
+    if (a.n <= kCombineFew) hipLaunchKernelGGL((combine_kernel<true, true>), dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
+    else hipLaunchKernelGGL((combine_kernel<true, false>), dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
+  if (a.n <= kCombineFew) hipLaunchKernelGGL((combine_kernel<false, true>), dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
+  else hipLaunchKernelGGL((combine_kernel<false, false>), dim3(blocks), dim3(256), 0, s, a, a.D / 4, lane_shift);
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && a.o_lowp != nullptr) {
     hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(n_vec)), dim3(256), 0, s, (const float4*)a.o_out,
